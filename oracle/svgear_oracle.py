@@ -1,0 +1,435 @@
+"""TEST INFRASTRUCTURE ONLY -- plain CPU oracle for the SVG-EAR attention hot path.
+
+Every function evaluates, slowly and in fp64 (numpy), what the paper defines; each cites
+the passage it follows. Only tests, the smoke check and the benchmark's cpu_baseline leg
+may import this package. It shares no code with the HIP library and never calls it.
+
+Stages (one attention head at a time; batch and head dimensions are independent,
+Appendix "Kernel Implementation Details"):
+
+  kmeans          Methodology, "Problem Formulation": Q and K are clustered, centroids
+                  are cluster means; V follows K's assignment ("Linear Compensation").
+  permute         Motivation, "Structured Redundancy": tokens of a cluster are laid out
+                  contiguously.
+  probe_errors    Eq. (7) (value-aware) or Eq. (5) (plain) summed over each block, with the
+                  per-row stabiliser of Algorithm 1 (first line: m_i = max_j S_ij).
+  route           "Error-Aware Routing": greedy by error-to-size ratio under the budget.
+  attention_comp  Eq. (1) and Eq. (6) evaluated literally.
+
+Readings taken where the paper is silent or inconsistent are listed next to each function.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against closed forms,
+brute force or library routines; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+from .build_oracle import build as _build_c
+
+_lib = None
+
+
+def _clib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(_build_c())
+        _lib.svgear_oracle_assign_f32.argtypes = [
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p,
+        ]
+        _lib.svgear_oracle_assign_f32.restype = None
+        _lib.svgear_oracle_max_threads.restype = ctypes.c_int
+    return _lib
+
+
+def host_threads() -> int:
+    """Threads the C assignment loop uses (OpenMP's maximum on this host)."""
+    return int(_clib().svgear_oracle_max_threads())
+
+
+# --------------------------------------------------------------------------- k-means
+
+
+def kmeans_assign(X: np.ndarray, cent: np.ndarray, return_scores: bool = False):
+    """Nearest-centroid label of every row, decided in the fixed fp32 order.
+
+    Squared Euclidean distance with the row's own norm dropped: score = |c|^2 - 2 x.c,
+    each dot product one fp32 fma chain over t = 0..d-1; ties go to the lowest index
+    (see assign_f32.c). X [n, d] and cent [C, d] are taken as float32 exactly.
+    """
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    cent = np.ascontiguousarray(cent, dtype=np.float32)
+    n, d = X.shape
+    C = cent.shape[0]
+    assert cent.shape[1] == d
+    labels = np.empty(n, dtype=np.int32)
+    best = np.empty(n, dtype=np.float32) if return_scores else None
+    _clib().svgear_oracle_assign_f32(
+        X.ctypes.data, n, d, cent.ctypes.data, C, labels.ctypes.data,
+        best.ctypes.data if return_scores else None,
+    )
+    return (labels, best) if return_scores else labels
+
+
+def cluster_means(X: np.ndarray, labels: np.ndarray, C: int, prev: np.ndarray):
+    """Mean of the members of each cluster (fp64 sums, rounded once to fp32).
+
+    "Problem Formulation": the centroid is the mean token of the cluster. A cluster with
+    no member keeps its previous centroid and reports count 0 (the paper does not treat
+    empty clusters; with weight |k_c| = 0 they contribute nothing downstream).
+    """
+    X64 = np.asarray(X, dtype=np.float64)
+    out = np.array(prev, dtype=np.float32, copy=True)
+    counts = np.zeros(C, dtype=np.int32)
+    for c in range(C):
+        sel = labels == c
+        k = int(sel.sum())
+        counts[c] = k
+        if k:
+            out[c] = (X64[sel].sum(axis=0) / k).astype(np.float32)
+    return out, counts
+
+
+def kmeans(X, init, iters: int, X2=None, prev2=None):
+    """`iters` Lloyd iterations (assign, then recompute means) from `init`.
+
+    Returns (centroids f32 [C,d], labels i32 [n], counts i32 [C], centroids2 or None).
+    The final centroids are the exact means of the final labels, as "Problem Formulation"
+    requires of q-bar and k-bar; centroids2 are the means of X2 (the values) under the same
+    labels ("Linear Compensation": V follows K's assignment). Fixed iteration count, no
+    early exit (the paper states neither; the benchmark configurations fix the count).
+    """
+    assert iters >= 1
+    cent = np.array(init, dtype=np.float32, copy=True)
+    C = cent.shape[0]
+    labels = counts = None
+    for _ in range(iters):
+        labels = kmeans_assign(X, cent)
+        cent, counts = cluster_means(X, labels, C, cent)
+    cent2 = None
+    if X2 is not None:
+        if prev2 is None:
+            prev2 = np.zeros((C, X2.shape[1]), dtype=np.float32)
+        cent2, _ = cluster_means(X2, labels, C, prev2)
+    return cent, labels, counts, cent2
+
+
+def inertia(X, cent, labels) -> float:
+    """Sum of squared distances of rows to their assigned centroid (fp64)."""
+    diff = np.asarray(X, np.float64) - np.asarray(cent, np.float64)[labels]
+    return float((diff * diff).sum())
+
+
+# --------------------------------------------------------------------------- permute
+
+
+def permute(labels: np.ndarray, C: int, n_tail: int = 0):
+    """Cluster-contiguous order: stable sort of token indices by label.
+
+    perm[p] is the original index of the token at sorted position p. The n_tail trailing
+    tokens (text tokens, which are not clustered) form pseudo-cluster C in original order.
+    offsets has C + 2 entries: cluster c occupies [offsets[c], offsets[c+1]) and the tail
+    [offsets[C], offsets[C+1]).
+    """
+    labels = np.asarray(labels)
+    n_clustered = labels.shape[0]
+    full = np.concatenate([labels.astype(np.int64), np.full(n_tail, C, dtype=np.int64)])
+    perm = np.argsort(full, kind="stable").astype(np.int32)
+    counts = np.bincount(full, minlength=C + 1)
+    offsets = np.zeros(C + 2, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    assert offsets[C] == n_clustered
+    return perm, offsets
+
+
+def unpermute_rows(Op: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """O[perm[p]] = Op[p]."""
+    out = np.empty_like(Op)
+    out[perm] = Op
+    return out
+
+
+# --------------------------------------------------------------------------- probe
+
+
+def probe_errors(qbar, kbar, vbar, Kp, Vp, k_offsets, scale: float, value_aware: bool = True):
+    """Estimated compensation error of every (query cluster a, key cluster b) block.
+
+    Value-aware, Eq. (7) summed over the keys of the block, every term carrying the row
+    factor exp(-m_a) that Algorithm 1 introduces (m_a = max_b qbar_a.kbar_b * scale over
+    non-empty b):
+
+        E[a,b] = sum_{j in b} || exp(Sbar_ab - m_a) vbar_b - exp(qbar_a.k_j*scale - m_a) v_j ||^2
+
+    Plain, Eq. (5): the same without the value vectors (scalar difference squared).
+    Returns (E [Cq,Ck], scores = E / |k_b| [Cq,Ck], m [Cq]). Because every query of cluster
+    a shares the estimate, the block's total error is |q_a| E[a,b] and its cost |q_a||k_b|,
+    so the error-to-cost ratio of "Error-Aware Routing" is E[a,b]/|k_b|. Empty key clusters
+    get E = score = 0 and are never routed nor compensated.
+
+    Readings: Algorithm 1 as printed starts its accumulator at ||Y||^2 instead of 0 and
+    rescales by exp(2(m_i - m_local)) at the end; Eq. (7) and the text ("aggregate the
+    estimated errors within each block") have no initial term, and moving an accumulator
+    from exp(-2 m_local) units to exp(-2 m_i) units needs exp(2(m_local - m_i)). This oracle
+    follows Eq. (7): it starts at 0 and needs no running maximum at all in fp64.
+    Kp, Vp are cluster-contiguous (k_offsets); only clustered keys enter.
+    """
+    qbar = np.asarray(qbar, np.float64)
+    kbar = np.asarray(kbar, np.float64)
+    vbar = np.asarray(vbar, np.float64)
+    Cq, Ck = qbar.shape[0], kbar.shape[0]
+    sizes = np.diff(np.asarray(k_offsets[: Ck + 1], np.int64))
+    Sbar = (qbar @ kbar.T) * scale
+    nonempty = sizes > 0
+    m = np.where(nonempty[None, :], Sbar, -np.inf).max(axis=1)
+    E = np.zeros((Cq, Ck), dtype=np.float64)
+    for b in range(Ck):
+        if not nonempty[b]:
+            continue
+        Kb = np.asarray(Kp[k_offsets[b]: k_offsets[b + 1]], np.float64)
+        Vb = np.asarray(Vp[k_offsets[b]: k_offsets[b + 1]], np.float64)
+        w = np.exp((qbar @ Kb.T) * scale - m[:, None])  # [Cq, nb]
+        W = np.exp(Sbar[:, b] - m)  # [Cq]
+        if value_aware:
+            diff = W[:, None, None] * vbar[b][None, None, :] - w[:, :, None] * Vb[None, :, :]
+            E[:, b] = (diff * diff).sum(axis=(1, 2))
+        else:
+            diff = W[:, None] - w
+            E[:, b] = (diff * diff).sum(axis=1)
+    scores = np.where(nonempty[None, :], E / np.maximum(sizes, 1)[None, :], 0.0)
+    return E, scores, m
+
+
+def probe_errors_streaming(qbar, kbar, vbar, Kp, Vp, k_offsets, scale: float):
+    """Algorithm 1's streaming form (running maximum, rescaling), with the two readings
+    stated in probe_errors applied; used only to pin probe_errors. Pure loops: small inputs.
+    """
+    qbar = np.asarray(qbar, np.float64)
+    kbar = np.asarray(kbar, np.float64)
+    vbar = np.asarray(vbar, np.float64)
+    Cq, Ck = qbar.shape[0], kbar.shape[0]
+    sizes = np.diff(np.asarray(k_offsets[: Ck + 1], np.int64))
+    S = (qbar @ kbar.T) * scale
+    m = np.where((sizes > 0)[None, :], S, -np.inf).max(axis=1)
+    E = np.zeros((Cq, Ck))
+    for i in range(Cq):
+        for j in range(Ck):
+            if sizes[j] == 0:
+                continue
+            Y = np.exp(S[i, j] - m[i]) * vbar[j]
+            m_loc = m[i]
+            e = 0.0
+            for t in range(k_offsets[j], k_offsets[j + 1]):
+                s = float(qbar[i] @ np.asarray(Kp[t], np.float64)) * scale
+                m_new = max(m_loc, s)
+                alpha = np.exp(m_loc - m_new)
+                e *= alpha * alpha
+                Y = Y * alpha
+                r = np.exp(s - m_new) * np.asarray(Vp[t], np.float64) - Y
+                e += float(r @ r)
+                m_loc = m_new
+            E[i, j] = e * np.exp(2.0 * (m_loc - m[i]))
+    return E
+
+
+# --------------------------------------------------------------------------- route
+
+
+def route(scores, q_sizes, k_sizes, budget: int, per_row: bool = False,
+          n_tail_q: int = 0, n_tail_k: int = 0):
+    """Greedy error-to-cost routing under a cost budget ("Error-Aware Routing").
+
+    Blocks with both sizes non-zero are ordered by score descending (NaN counts as +inf),
+    equal scores by ascending linear index a*Ck + b. The cost of a block is |q_a||k_b|
+    (integer). Walking that order, blocks are routed while the running cost stays within
+    the budget; the walk stops at the first block that does not fit (the paper says
+    "until the budget is exhausted"; stop-at-first-misfit is the reading taken).
+
+    Tail (text) tokens form one extra query row (index Cq) and one extra key column
+    (index Ck); their blocks are always routed and are charged to the budget first (if
+    they alone exceed it, nothing else is routed).
+
+    per_row=True applies the same rule independently to each query cluster a with budget
+    floor(budget * |q_a| / Nq_total) (the granularity of the paper's implementation,
+    Experiments, "Implementation").
+
+    Returns (mask bool [R, Cc], row_ptr i32 [R+1], col_idx i32, routed_cost int) with
+    R = Cq + (n_tail_q > 0), Cc = Ck + (n_tail_k > 0); col_idx ascending within a row.
+    """
+    scores = np.asarray(scores)
+    Cq, Ck = scores.shape
+    qs = [int(v) for v in q_sizes[:Cq]] + ([int(n_tail_q)] if n_tail_q > 0 else [])
+    ks = [int(v) for v in k_sizes[:Ck]] + ([int(n_tail_k)] if n_tail_k > 0 else [])
+    R, Cc = len(qs), len(ks)
+    nq_total = sum(qs)
+    mask = np.zeros((R, Cc), dtype=bool)
+    row_forced = [0] * R
+    for a in range(R):
+        for b in range(Cc):
+            forced = (a >= Cq) or (b >= Ck)
+            if forced and qs[a] > 0 and ks[b] > 0:
+                mask[a, b] = True
+                row_forced[a] += qs[a] * ks[b]
+    routed_cost = sum(row_forced)
+
+    def key(a, b):
+        s = float(scores[a, b])
+        if np.isnan(s):
+            s = np.inf
+        return (-s, a * Ck + b)
+
+    def greedy(items, remaining):
+        spent = 0
+        for (a, b) in sorted(items, key=lambda ab: key(*ab)):
+            c = qs[a] * ks[b]
+            if spent + c > remaining:
+                break
+            spent += c
+            mask[a, b] = True
+        return spent
+
+    if per_row:
+        for a in range(Cq):
+            if qs[a] == 0:
+                continue
+            rem = max((int(budget) * qs[a]) // max(nq_total, 1) - row_forced[a], 0)
+            routed_cost += greedy([(a, b) for b in range(Ck) if ks[b] > 0], rem)
+    else:
+        rem = max(int(budget) - routed_cost, 0)
+        items = [(a, b) for a in range(Cq) for b in range(Ck) if qs[a] > 0 and ks[b] > 0]
+        routed_cost += greedy(items, rem)
+
+    row_ptr = np.zeros(R + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(mask.sum(axis=1))
+    col_idx = np.concatenate([np.nonzero(mask[a])[0] for a in range(R)]).astype(np.int32) \
+        if R else np.zeros(0, np.int32)
+    return mask, row_ptr, col_idx, int(routed_cost)
+
+
+# --------------------------------------------------------------------------- attention
+
+
+def dense_attention(Q, K, V, scale: float):
+    """softmax(Q K^T * scale) V in fp64 (A_full of Eq. (2))."""
+    Q, K, V = (np.asarray(t, np.float64) for t in (Q, K, V))
+    L = (Q @ K.T) * scale
+    L -= L.max(axis=1, keepdims=True)
+    P = np.exp(L)
+    return (P / P.sum(axis=1, keepdims=True)) @ V
+
+
+def attention_map_comp(Q, K, lab_q, lab_k, kbar, mask, scale: float):
+    """The compensated attention map of Eq. (1), rows [n_q, n_k], and the boolean
+    per-entry mask M. Entries with M = 1 use the exact logit, the others the logit against
+    the key's cluster mean (the text after Eq. (1): the product with M selects, it does
+    not multiply a logit by zero)."""
+    Q, K, kbar = (np.asarray(t, np.float64) for t in (Q, K, kbar))
+    M = np.asarray(mask)[np.asarray(lab_q)][:, np.asarray(lab_k)]
+    exact = (Q @ K.T) * scale
+    comp = ((Q @ kbar.T) * scale)[:, np.asarray(lab_k)]
+    L = np.where(M, exact, comp)
+    L -= L.max(axis=1, keepdims=True)
+    P = np.exp(L)
+    return P / P.sum(axis=1, keepdims=True), M
+
+
+def attention_comp(Q, K, V, lab_q, lab_k, kbar, vbar, mask, scale: float, row_chunk: int = 512):
+    """Sparse attention output with linear compensation, Eq. (1) + Eq. (6), literally:
+
+        A = softmax(where(M, Q K^T, Q Kbar^T) * scale);  O = (A*M) V + (A*(1-M)) Vbar
+
+    lab_q[i] / lab_k[j] are the cluster (row / column of `mask`) of each query / key;
+    kbar, vbar hold one row per key column of `mask` (rows of always-routed columns, e.g.
+    the text tail, are never read through M = 0 and may hold anything finite).
+    Works on any token order; pass permuted tensors with permuted labels to get the
+    permuted output.
+    """
+    V64 = np.asarray(V, np.float64)
+    vbar_rows = np.asarray(vbar, np.float64)[np.asarray(lab_k)]
+    out = np.empty((Q.shape[0], V64.shape[1]), dtype=np.float64)
+    for s in range(0, Q.shape[0], row_chunk):
+        e = min(s + row_chunk, Q.shape[0])
+        A, M = attention_map_comp(Q[s:e], K, lab_q[s:e], lab_k, kbar, mask, scale)
+        out[s:e] = (A * M) @ V64 + (A * ~M) @ vbar_rows
+    return out
+
+
+def attention_two_stage(Q, K, V, lab_q, lab_k, kbar, vbar, k_sizes, mask, scale: float):
+    """Algorithm 2's form: exact attention over routed keys giving (O, LSE), then every
+    skipped non-empty cluster merged as one pseudo-key with logit q.kbar*scale + ln|k_c|
+    and value vbar by online softmax. Reading: the algorithm as printed never initialises
+    its accumulator; starting from acc = O with l = 1, m = LSE is the consistent choice,
+    and a row with nothing routed starts empty. Used only to pin attention_comp.
+    Pure loops: small inputs.
+    """
+    Q, K, V, kbar, vbar = (np.asarray(t, np.float64) for t in (Q, K, V, kbar, vbar))
+    nq, d = Q.shape[0], V.shape[1]
+    out = np.zeros((nq, d))
+    lab_k = np.asarray(lab_k)
+    for i in range(nq):
+        a = lab_q[i]
+        sel = np.asarray(mask)[a][lab_k]
+        if sel.any():
+            l = (K[sel] @ Q[i]) * scale
+            mx = l.max()
+            p = np.exp(l - mx)
+            acc = (p @ V[sel]) / p.sum()
+            m_i = mx + np.log(p.sum())
+            l_i = 1.0
+        else:
+            acc = np.zeros(d)
+            m_i = -np.inf
+            l_i = 0.0
+        for j in range(kbar.shape[0]):
+            if mask[a][j] or k_sizes[j] == 0:
+                continue
+            s = float(Q[i] @ kbar[j]) * scale + np.log(k_sizes[j])
+            m_new = max(m_i, s)
+            alpha = np.exp(m_i - m_new) if np.isfinite(m_i) else 0.0
+            p = np.exp(s - m_new)
+            l_i = l_i * alpha + p
+            acc = acc * alpha + p * vbar[j]
+            m_i = m_new
+        out[i] = acc / l_i
+    return out
+
+
+# --------------------------------------------------------------------------- whole path
+
+
+def scale_of(d: int) -> float:
+    """1/sqrt(d) (Motivation: logits are q k^T / sqrt(d))."""
+    return 1.0 / float(np.sqrt(np.float64(d)))
+
+
+def hot_path_head(Q, K, V, init_q, init_k, iters: int, budget: int, n_tail: int = 0,
+                  value_aware: bool = True, per_row: bool = False):
+    """All stages for one head, in the order the method runs them; returns a dict with
+    every intermediate (used by the end-to-end parity test and the cpu_baseline timing).
+    Q, K, V are [N, d] arrays (any float dtype holding the exact input values)."""
+    Q32, K32, V32 = (np.asarray(t, np.float32) for t in (Q, K, V))
+    N, d = Q32.shape
+    nv = N - n_tail
+    Cq, Ck = init_q.shape[0], init_k.shape[0]
+    scale = scale_of(d)
+    qbar, lab_q, qcnt, _ = kmeans(Q32[:nv], init_q, iters)
+    kbar, lab_k, kcnt, vbar = kmeans(K32[:nv], init_k, iters, X2=V32[:nv])
+    perm_q, qoff = permute(lab_q, Cq, n_tail)
+    perm_k, koff = permute(lab_k, Ck, n_tail)
+    Qp, Kp, Vp = Q32[perm_q], K32[perm_k], V32[perm_k]
+    E, scores, m = probe_errors(qbar, kbar, vbar, Kp, Vp, koff, scale, value_aware)
+    mask, row_ptr, col_idx, cost = route(scores, qcnt, kcnt, budget, per_row, n_tail, n_tail)
+    lq = np.repeat(np.arange(Cq + 1), np.diff(qoff))
+    lk = np.repeat(np.arange(Ck + 1), np.diff(koff))
+    kb = np.concatenate([kbar, np.zeros((1, d), np.float32)]) if n_tail else kbar
+    vb = np.concatenate([vbar, np.zeros((1, d), np.float32)]) if n_tail else vbar
+    Op = attention_comp(Qp, Kp, Vp, lq, lk, kb, vb, mask, scale)
+    O = unpermute_rows(Op, perm_q)
+    return dict(qbar=qbar, kbar=kbar, vbar=vbar, lab_q=lab_q, lab_k=lab_k, qcnt=qcnt, kcnt=kcnt,
+                perm_q=perm_q, perm_k=perm_k, qoff=qoff, koff=koff, E=E, scores=scores, m=m,
+                mask=mask, row_ptr=row_ptr, col_idx=col_idx, routed_cost=cost, Op=Op, O=O)

@@ -1,0 +1,235 @@
+"""Pins for the oracle's probe (Eq. (5), Eq. (7), Algorithm 1) and router
+("Error-Aware Routing") -- CPU only."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import svgear_oracle as orc
+
+
+def _setup(seed=0, Cq=5, Ck=7, d=8, n=60, empty=None):
+    rng = np.random.default_rng(seed)
+    qbar = rng.standard_normal((Cq, d))
+    lab = np.sort(rng.integers(0, Ck, n))
+    if empty is not None:
+        lab = lab[lab != empty]
+    n = lab.shape[0]
+    centers_k = rng.standard_normal((Ck, d))
+    centers_v = rng.standard_normal((Ck, d))
+    Kp = centers_k[lab] + 0.3 * rng.standard_normal((n, d))
+    Vp = centers_v[lab] + 0.3 * rng.standard_normal((n, d))
+    off = np.zeros(Ck + 2, np.int32)
+    off[1: Ck + 1] = np.cumsum(np.bincount(lab, minlength=Ck))
+    off[Ck + 1] = off[Ck]
+    kbar = np.zeros((Ck, d))
+    vbar = np.zeros((Ck, d))
+    for b in range(Ck):
+        if off[b + 1] > off[b]:
+            kbar[b] = Kp[off[b]: off[b + 1]].mean(0)
+            vbar[b] = Vp[off[b]: off[b + 1]].mean(0)
+    return qbar, kbar, vbar, Kp, Vp, off, lab
+
+
+def test_probe_equals_entrywise_eq7_bruteforce():
+    # Eq. (7) verbatim for every (query, key) entry with qbar_i per row, summed per block
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(1, empty=3)
+    d = qbar.shape[1]
+    scale = 1 / np.sqrt(d)
+    E, scores, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, scale, True)
+    q_sizes = np.array([3, 1, 4, 2, 5])
+    row_cluster = np.repeat(np.arange(5), q_sizes)
+    tot = np.zeros_like(E)
+    for i, a in enumerate(row_cluster):
+        for j, b in enumerate(lab):
+            lhs = np.exp(qbar[a] @ kbar[b] * scale) * vbar[b]
+            rhs = np.exp(qbar[a] @ Kp[j] * scale) * Vp[j]
+            tot[a, b] += ((lhs - rhs) ** 2).sum()
+    sizes = np.diff(off[:8])
+    for a in range(5):
+        for b in range(7):
+            if sizes[b] == 0:
+                assert E[a, b] == 0 and scores[a, b] == 0
+                continue
+            ratio = tot[a, b] / (q_sizes[a] * sizes[b])  # error-to-cost ratio of the text
+            assert np.isclose(ratio * np.exp(-2 * m[a]), scores[a, b], rtol=1e-10)
+
+
+def test_probe_plain_equals_entrywise_eq5():
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(2)
+    scale = 0.37
+    E, scores, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, scale, False)
+    for a in range(qbar.shape[0]):
+        tot = np.zeros(7)
+        for j, b in enumerate(lab):
+            tot[b] += (np.exp(qbar[a] @ kbar[b] * scale) - np.exp(qbar[a] @ Kp[j] * scale)) ** 2
+        assert np.allclose(tot * np.exp(-2 * m[a]), E[a], rtol=1e-10)
+
+
+def test_probe_zero_when_block_is_constant():
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(3)
+    Kp = kbar[lab].copy()
+    Vp = vbar[lab].copy()
+    E, scores, _ = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, 0.3, True)
+    assert np.abs(E).max() < 1e-24
+    # only the values constant: error remains (keys still differ from their mean)
+    _, _, _, Kp2, _, _, _ = _setup(3)
+    E2, _, _ = orc.probe_errors(qbar, kbar, vbar, Kp2, Vp, off, 0.3, True)
+    assert E2.max() > 1e-6
+
+
+def test_probe_row_stabiliser_is_exp_minus_2m():
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(4)
+    scale = 0.5
+    E, _, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, scale, True)
+    S = qbar @ kbar.T * scale
+    assert np.allclose(m, S.max(1))
+    # un-stabilised Eq. (7) block sums
+    for a in range(qbar.shape[0]):
+        for b in range(7):
+            sl = slice(off[b], off[b + 1])
+            raw = ((np.exp(S[a, b]) * vbar[b][None] - np.exp(Kp[sl] @ qbar[a] * scale)[:, None] * Vp[sl]) ** 2).sum()
+            assert np.isclose(raw * np.exp(-2 * m[a]), E[a, b], rtol=1e-10)
+
+
+def test_probe_streaming_algorithm1_matches_direct():
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(5, empty=2)
+    # make some keys exceed every centroid logit so the running maximum really moves
+    Kp[::7] *= 4.0
+    E, _, _ = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, 0.4, True)
+    Es = orc.probe_errors_streaming(qbar, kbar, vbar, Kp, Vp, off, 0.4)
+    assert np.allclose(E, Es, rtol=1e-11, atol=0)
+
+
+def test_probe_printed_initial_term_differs_by_exp2S_vbar2():
+    # Algorithm 1 as printed starts E at ||Y||^2; that adds exp(2(S-m))||vbar||^2 per block
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(6)
+    scale = 0.4
+    E, _, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, scale, True)
+    S = qbar @ kbar.T * scale
+    extra = np.exp(2 * (S - m[:, None])) * (vbar ** 2).sum(1)[None]
+    assert extra.min() > 0  # so the two readings are distinguishable
+    assert np.all(E + extra > E)
+
+
+def test_probe_expanded_square_identity():
+    qbar, kbar, vbar, Kp, Vp, off, lab = _setup(7)
+    scale = 0.4
+    E, _, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, scale, True)
+    S = qbar @ kbar.T * scale
+    for a in range(qbar.shape[0]):
+        for b in range(7):
+            sl = slice(off[b], off[b + 1])
+            w = np.exp(Kp[sl] @ qbar[a] * scale - m[a])
+            W = np.exp(S[a, b] - m[a])
+            ex = (w * w * (Vp[sl] ** 2).sum(1)).sum() - 2 * W * (w * (Vp[sl] @ vbar[b])).sum() \
+                + (off[b + 1] - off[b]) * W * W * (vbar[b] ** 2).sum()
+            assert np.isclose(ex, E[a, b], rtol=1e-8, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- route
+
+
+def test_route_extremes_and_budget_invariant():
+    rng = np.random.default_rng(0)
+    Cq, Ck = 6, 9
+    scores = rng.random((Cq, Ck))
+    qs = rng.integers(1, 20, Cq)
+    ks = rng.integers(1, 20, Ck)
+    total = int(qs.sum() * ks.sum())
+    mask, rp, ci, cost = orc.route(scores, qs, ks, total)
+    assert mask.all() and cost == total and rp[-1] == Cq * Ck
+    mask, rp, ci, cost = orc.route(scores, qs, ks, 0)
+    assert not mask.any() and cost == 0 and rp[-1] == 0
+    for budget in [total // 7, total // 3, total // 2]:
+        mask, rp, ci, cost = orc.route(scores, qs, ks, budget)
+        assert cost == int((np.outer(qs, ks) * mask).sum()) <= budget
+        # the best unrouted block is the one the walk stopped at: it must not fit
+        un = [(-scores[a, b], a * Ck + b, a, b) for a in range(Cq) for b in range(Ck) if not mask[a, b]]
+        _, _, a, b = min(un)
+        assert cost + qs[a] * ks[b] > budget
+        # every routed block outranks every unrouted one
+        worst_routed = max((-scores[a, b], a * Ck + b) for a in range(Cq) for b in range(Ck) if mask[a, b])
+        assert worst_routed < min(un)[:2]
+        # CSR consistent with the mask, ascending columns
+        for a in range(Cq):
+            assert ci[rp[a]: rp[a + 1]].tolist() == np.nonzero(mask[a])[0].tolist()
+
+
+def test_route_ties_lowest_index_and_nan_first():
+    scores = np.array([[1.0, 1.0, 1.0], [1.0, np.nan, 0.5]])
+    qs, ks = [2, 2], [3, 3, 3]
+    mask, _, _, cost = orc.route(scores, qs, ks, 6 * 3)  # room for three blocks
+    assert mask.tolist() == [[True, True, False], [False, True, False]]
+    assert cost == 18
+
+
+def test_route_skips_empty_clusters():
+    scores = np.full((3, 3), 5.0)
+    mask, rp, ci, cost = orc.route(scores, [4, 0, 4], [0, 2, 2], 10 ** 6)
+    assert mask.tolist() == [[False, True, True], [False, False, False], [False, True, True]]
+    assert cost == 32
+
+
+def test_route_greedy_vs_bruteforce_knapsack():
+    # all 2^16 masks of a 4x4 block grid. Equal costs: greedy by ratio is optimal.
+    rng = np.random.default_rng(11)
+    scores = rng.random((4, 4))
+    qs, ks = [3, 3, 3, 3], [5, 5, 5, 5]
+    val = scores * 15 * 3  # block value = |q_a| * E_ab = |q_a||k_b| * score
+    for nblocks in [0, 1, 5, 16]:
+        budget = 15 * nblocks + 7
+        mask, _, _, cost = orc.route(scores, qs, ks, budget)
+        got = (val * mask).sum()
+        best = 0.0
+        for bits in range(1 << 16):
+            if bin(bits).count("1") * 15 <= budget:
+                sel = np.array([(bits >> t) & 1 for t in range(16)], bool).reshape(4, 4)
+                best = max(best, (val * sel).sum())
+        assert np.isclose(got, best)
+    # unequal costs: the classical greedy guarantee OPT <= greedy + value(first rejected)
+    qs, ks = [1, 4, 2, 6], [3, 1, 5, 2]
+    cost_m = np.outer(qs, ks)
+    val = scores * cost_m
+    budget = int(cost_m.sum() * 0.4)
+    mask, _, _, cost = orc.route(scores, qs, ks, budget)
+    order = sorted(((-scores[a, b], a * 4 + b) for a in range(4) for b in range(4) if not mask[a, b]))
+    a, b = divmod(order[0][1], 4)
+    best = 0.0
+    flat_c, flat_v = cost_m.ravel(), val.ravel()
+    for bits in range(1 << 16):
+        sel = np.array([(bits >> t) & 1 for t in range(16)], bool)
+        if flat_c[sel].sum() <= budget:
+            best = max(best, flat_v[sel].sum())
+    assert (val * mask).sum() <= best <= (val * mask).sum() + val[a, b] + 1e-12
+
+
+def test_route_tail_blocks_forced_and_charged():
+    rng = np.random.default_rng(12)
+    scores = rng.random((3, 4))
+    qs, ks = [5, 6, 7], [2, 3, 4, 5]
+    tq = tk = 3
+    nq, nk = sum(qs) + tq, sum(ks) + tk
+    forced = tq * nk + nq * tk - tq * tk
+    mask, rp, ci, cost = orc.route(scores, qs, ks, forced + 5 * 2 - 1, n_tail_q=tq, n_tail_k=tk)
+    assert mask.shape == (4, 5)
+    assert mask[3].all() and mask[:, 4].all()
+    assert cost >= forced
+    mask2, _, _, cost2 = orc.route(scores, qs, ks, 0, n_tail_q=tq, n_tail_k=tk)
+    assert cost2 == forced and mask2[:3, :4].sum() == 0
+
+
+def test_route_per_row_budgets():
+    rng = np.random.default_rng(13)
+    scores = rng.random((4, 6))
+    qs, ks = [3, 5, 2, 7], [4, 4, 2, 6, 1, 3]
+    nq, nk = sum(qs), sum(ks)
+    budget = int(0.5 * nq * nk)
+    mask, _, _, cost = orc.route(scores, qs, ks, budget, per_row=True)
+    for a in range(4):
+        row_budget = budget * qs[a] // nq
+        row_cost = int((np.array(ks) * mask[a]).sum()) * qs[a]
+        assert row_cost <= row_budget
+        m1, _, _, c1 = orc.route(scores[a: a + 1], [qs[a]], ks, row_budget)
+        assert m1[0].tolist() == mask[a].tolist()
+    assert cost == int((np.outer(qs, ks) * mask).sum())
