@@ -1,0 +1,256 @@
+"""ctypes binding of libsvgear.so: argument marshalling only.
+
+Each function mirrors one entry point of include/svgear.h, allocates outputs and the
+workspace with torch on the inputs' device, and enqueues the call on torch's current
+stream. No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+PROBE_PLAIN = 1
+ROUTE_PER_ROW = 2
+USE_GIVEN_SCORES = 4
+
+EXPORTED_SYMBOLS = [
+    "svgear_version", "svgear_last_hip_error",
+    "svgear_kmeans_workspace", "svgear_kmeans",
+    "svgear_permute_workspace", "svgear_permute",
+    "svgear_probe_route_workspace", "svgear_probe_route",
+    "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp",
+    "svgear_unpermute",
+]
+
+_c = ctypes
+_vp, _i, _i64, _sz, _f, _u = _c.c_void_p, _c.c_int, _c.c_int64, _c.c_size_t, _c.c_float, _c.c_uint
+_I64x3 = _c.c_int64 * 3
+
+
+class SvgearError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libsvgear.so")
+
+
+def load_library():
+    """Loads the built library; builds it first only if no built library exists."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        from .build import build
+
+        build()
+    lib = ctypes.CDLL(path)
+    lib.svgear_version.restype = _i
+    lib.svgear_last_hip_error.restype = _i
+    lib.svgear_kmeans_workspace.restype = _sz
+    lib.svgear_kmeans_workspace.argtypes = [_i, _i, _i64, _i, _i]
+    lib.svgear_kmeans.restype = _i
+    lib.svgear_kmeans.argtypes = [_vp, _vp, _i, _i, _i, _i64, _i64, _i, _c.POINTER(_c.c_int64), _i, _i,
+                                  _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.svgear_permute_workspace.restype = _sz
+    lib.svgear_permute_workspace.argtypes = [_i, _i, _i64, _i]
+    lib.svgear_permute.restype = _i
+    lib.svgear_permute.argtypes = [_vp, _i, _i, _i64, _i64, _i, _vp, _vp, _i, _c.POINTER(_vp),
+                                   _c.POINTER(_I64x3), _c.POINTER(_vp), _i, _i, _vp, _sz, _vp]
+    lib.svgear_probe_route_workspace.restype = _sz
+    lib.svgear_probe_route_workspace.argtypes = [_i, _i, _i64, _i, _i, _i]
+    lib.svgear_probe_route.restype = _i
+    lib.svgear_probe_route.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _i64, _i64, _i, _i, _i,
+                                       _i64, _f, _u, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.svgear_sparse_attn_comp_workspace.restype = _sz
+    lib.svgear_sparse_attn_comp_workspace.argtypes = [_i, _i, _i64, _i64, _i, _i, _i]
+    lib.svgear_sparse_attn_comp.restype = _i
+    lib.svgear_sparse_attn_comp.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i64,
+                                            _i64, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]
+    lib.svgear_unpermute.restype = _i
+    lib.svgear_unpermute.argtypes = [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _c.POINTER(_c.c_int64), _vp]
+    _LIB = lib
+    return lib
+
+
+_STATUS = {-1: "invalid argument", -2: "workspace too small", -3: "HIP runtime error", -4: "unsupported"}
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        extra = f" (hip error {load_library().svgear_last_hip_error()})" if rc == -3 else ""
+        raise SvgearError(f"{what} failed: {_STATUS.get(rc, rc)}{extra}")
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.bfloat16:
+        return 1
+    raise SvgearError(f"unsupported dtype {t.dtype}")
+
+
+def _need_gpu(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise SvgearError("svgear needs device tensors: there is no CPU path")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _strides4(t: torch.Tensor):
+    assert t.dim() == 4 and t.stride(3) == 1, "expected [B,H,N,d] with contiguous d"
+    return _I64x3(t.stride(0), t.stride(1), t.stride(2))
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def kmeans(x: torch.Tensor, centroids: torch.Tensor, iters: int, n_tail: int = 0,
+           x2: Optional[torch.Tensor] = None):
+    """svgear_kmeans. x [B,H,N,d]; centroids [B,H,C,d] fp32 (updated in place).
+    Returns (labels [B,H,N-n_tail] i32, counts [B,H,C] i32, centroids2 or None)."""
+    _need_gpu(x, centroids, x2)
+    lib = load_library()
+    B, H, N, d = x.shape
+    C = centroids.shape[2]
+    assert centroids.dtype == torch.float32 and centroids.is_contiguous()
+    if x2 is not None:
+        assert x2.shape == x.shape and x2.stride() == x.stride() and x2.dtype == x.dtype
+    labels = torch.empty(B, H, N - n_tail, dtype=torch.int32, device=x.device)
+    counts = torch.empty(B, H, C, dtype=torch.int32, device=x.device)
+    c2 = torch.zeros(B, H, C, d, dtype=torch.float32, device=x.device) if x2 is not None else None
+    ws = _ws(lib.svgear_kmeans_workspace(B, H, N, d, C), x.device)
+    st = _strides4(x)
+    rc = lib.svgear_kmeans(_ptr(x), _ptr(x2), _dt(x), B, H, N, n_tail, d, st, C, iters, _ptr(centroids),
+                           _ptr(c2), _ptr(labels), _ptr(counts), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "svgear_kmeans")
+    return labels, counts, c2
+
+
+def permute(labels: torch.Tensor, C: int, tensors: Sequence[torch.Tensor] = (), n_tail: int = 0):
+    """svgear_permute. Returns (perm [B,H,N] i32, offsets [B,H,C+2] i32, [permuted tensors])."""
+    _need_gpu(labels, *tensors)
+    lib = load_library()
+    B, H, nv = labels.shape
+    N = nv + n_tail
+    assert labels.dtype == torch.int32 and labels.is_contiguous()
+    perm = torch.empty(B, H, N, dtype=torch.int32, device=labels.device)
+    offsets = torch.empty(B, H, C + 2, dtype=torch.int32, device=labels.device)
+    n = len(tensors)
+    d, dt = 64, 0
+    outs = []
+    if n:
+        d, dt = tensors[0].shape[3], _dt(tensors[0])
+        for t in tensors:
+            assert t.shape == (B, H, N, d) and _dt(t) == dt
+        outs = [torch.empty(B, H, N, d, dtype=t.dtype, device=t.device) for t in tensors]
+    src = (_vp * max(n, 1))(*[t.data_ptr() for t in tensors])
+    dst = (_vp * max(n, 1))(*[t.data_ptr() for t in outs])
+    sst = (_I64x3 * max(n, 1))(*[_strides4(t) for t in tensors])
+    ws = _ws(lib.svgear_permute_workspace(B, H, N, C), labels.device)
+    rc = lib.svgear_permute(_ptr(labels), B, H, N, n_tail, C, _ptr(perm), _ptr(offsets), n, src, sst, dst, dt, d,
+                            _ptr(ws), ws.numel(), _stream())
+    _check(rc, "svgear_permute")
+    return perm, offsets, outs
+
+
+def probe_route(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, budget_cost: int, scale: float,
+                flags: int = 0, scores: Optional[torch.Tensor] = None, Nq: Optional[int] = None):
+    """svgear_probe_route. Returns dict(scores, mask_bits, row_ptr, col_idx, routed_cost)."""
+    _need_gpu(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, scores)
+    lib = load_library()
+    B, H, Cq, d = qbar.shape
+    Ck = kbar.shape[2]
+    Nk = kp.shape[2]
+    Nq = Nk if Nq is None else int(Nq)
+    dev = qbar.device
+    if scores is None:
+        scores = torch.empty(B, H, Cq, Ck, dtype=torch.float32, device=dev)
+    assert scores.shape == (B, H, Cq, Ck) and scores.dtype == torch.float32 and scores.is_contiguous()
+    W = (Ck + 1 + 31) // 32
+    mask_bits = torch.empty(B, H, Cq + 1, W, dtype=torch.int32, device=dev)
+    row_ptr = torch.empty(B, H, Cq + 2, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(B, H, (Cq + 1) * (Ck + 1), dtype=torch.int32, device=dev)
+    routed_cost = torch.empty(B, H, dtype=torch.int64, device=dev)
+    ws = _ws(lib.svgear_probe_route_workspace(B, H, Nk, d, Cq, Ck), dev)
+    for t in (qbar, kbar, vbar, kp, vp, q_offsets, k_offsets):
+        assert t.is_contiguous()
+    rc = lib.svgear_probe_route(_ptr(qbar), _ptr(kbar), _ptr(vbar), _ptr(kp), _ptr(vp), _dt(kp), _ptr(q_offsets),
+                                _ptr(k_offsets), B, H, Nq, Nk, d, Cq, Ck, int(budget_cost), float(scale),
+                                int(flags), _ptr(scores), _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx),
+                                _ptr(routed_cost), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "svgear_probe_route")
+    return dict(scores=scores, mask_bits=mask_bits, row_ptr=row_ptr, col_idx=col_idx, routed_cost=routed_cost)
+
+
+def sparse_attn_comp(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, scale: float,
+                     want_lse: bool = False, ws: Optional[torch.Tensor] = None):
+    """svgear_sparse_attn_comp. Returns (op [B,H,Nq,d], lse or None)."""
+    _need_gpu(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx)
+    lib = load_library()
+    B, H, Nq, d = qp.shape
+    Nk = kp.shape[2]
+    Cq = q_offsets.shape[2] - 2
+    Ck = k_offsets.shape[2] - 2
+    for t in (qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx):
+        assert t.is_contiguous()
+    op = torch.empty_like(qp)
+    lse = torch.empty(B, H, Nq, dtype=torch.float32, device=qp.device) if want_lse else None
+    if ws is None:
+        ws = _ws(lib.svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck), qp.device)
+    rc = lib.svgear_sparse_attn_comp(_ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar),
+                                     _ptr(q_offsets), _ptr(k_offsets), _ptr(mask_bits), _ptr(row_ptr),
+                                     _ptr(col_idx), B, H, Nq, Nk, d, Cq, Ck, float(scale), _ptr(op), _ptr(lse),
+                                     _ptr(ws), ws.numel(), _stream())
+    _check(rc, "svgear_sparse_attn_comp")
+    return op, lse
+
+
+def unpermute(op: torch.Tensor, perm: torch.Tensor, out: Optional[torch.Tensor] = None):
+    """svgear_unpermute: out[b,h,perm[p]] = op[b,h,p]."""
+    _need_gpu(op, perm, out)
+    lib = load_library()
+    B, H, N, d = op.shape
+    assert op.is_contiguous() and perm.is_contiguous()
+    if out is None:
+        out = torch.empty_like(op)
+    rc = lib.svgear_unpermute(_ptr(op), _ptr(perm), _dt(op), B, H, N, d, _ptr(out), _strides4(out), _stream())
+    _check(rc, "svgear_unpermute")
+    return out
+
+
+def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tail: int = 0, flags: int = 0,
+                    scale: Optional[float] = None):
+    """One pass of the whole hot path over a batch of heads: the five library calls in order.
+
+    init_q [B,H,Cq,d], init_k [B,H,Ck,d] fp32 are the starting centroids (updated in place,
+    so a caller can carry them to the next denoising step). Returns (O, intermediates)."""
+    B, H, N, d = Q.shape
+    if scale is None:
+        scale = float(d) ** -0.5
+    Cq, Ck = init_q.shape[2], init_k.shape[2]
+    lab_q, qcnt, _ = kmeans(Q, init_q, iters, n_tail)
+    lab_k, kcnt, vbar = kmeans(K, init_k, iters, n_tail, x2=V)
+    perm_q, qoff, (Qp,) = permute(lab_q, Cq, [Q], n_tail)
+    perm_k, koff, (Kp, Vp) = permute(lab_k, Ck, [K, V], n_tail)
+    r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags)
+    Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
+    O = unpermute(Op, perm_q)
+    r.update(lab_q=lab_q, lab_k=lab_k, qcnt=qcnt, kcnt=kcnt, qbar=init_q, kbar=init_k, vbar=vbar, perm_q=perm_q,
+             perm_k=perm_k, qoff=qoff, koff=koff, Qp=Qp, Kp=Kp, Vp=Vp, Op=Op)
+    return O, r

@@ -1,0 +1,214 @@
+// Cluster permutation: stable counting sort of token indices by cluster label, row
+// gather into cluster-contiguous order, and the inverse row scatter.
+// Paper: Motivation, "Structured Redundancy in Attention Computation" (tokens of a cluster
+// are laid out contiguously so the attention map becomes a grid of blocks).
+//
+// The sort is integer-only and deterministic: per-chunk histograms (LDS integer atomics),
+// an exclusive scan over (cluster, chunk), then a stable in-chunk ranking without atomics.
+#include "common.h"
+
+namespace svgear {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ int token_label(const int32_t* labels, int64_t i, int64_t nv, int C) {
+  if (i >= nv) return C;  // tail pseudo-cluster
+  int l = labels[i];
+  return l < 0 ? 0 : (l >= C ? C - 1 : l);  // out-of-range labels are clamped
+}
+
+__global__ void __launch_bounds__(kThreads)
+hist_kernel(const int32_t* __restrict__ labels, int64_t N, int64_t nv, int C, int nchunks,
+            int32_t* __restrict__ chunk_hist) {
+  extern __shared__ int32_t h[];
+  const int bh = blockIdx.y, chunk = blockIdx.x;
+  for (int c = threadIdx.x; c <= C; c += kThreads) h[c] = 0;
+  __syncthreads();
+  const int64_t lo = (int64_t)chunk * kSortChunk;
+  const int64_t hi = min(N, lo + kSortChunk);
+  const int32_t* lab = labels + (int64_t)bh * nv;
+  for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) atomicAdd(&h[token_label(lab, i, nv, C)], 1);
+  __syncthreads();
+  int32_t* out = chunk_hist + ((int64_t)bh * nchunks + chunk) * (C + 1);
+  for (int c = threadIdx.x; c <= C; c += kThreads) out[c] = h[c];
+}
+
+// Turns per-chunk histograms into per-chunk start positions and writes the offsets.
+__global__ void __launch_bounds__(kThreads)
+scan_kernel(int32_t* __restrict__ chunk_hist, int64_t N, int C, int nchunks,
+            int32_t* __restrict__ offsets) {
+  extern __shared__ int32_t tot[];  // C+1 totals, then C+1 exclusive offsets
+  int32_t* offs = tot + (C + 1);
+  const int bh = blockIdx.x;
+  int32_t* hist = chunk_hist + (int64_t)bh * nchunks * (C + 1);
+  for (int c = threadIdx.x; c <= C; c += kThreads) {
+    int32_t run = 0;
+    for (int k = 0; k < nchunks; ++k) {
+      int32_t v = hist[(int64_t)k * (C + 1) + c];
+      hist[(int64_t)k * (C + 1) + c] = run;
+      run += v;
+    }
+    tot[c] = run;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int32_t run = 0;
+    for (int c = 0; c <= C; ++c) {
+      offs[c] = run;
+      run += tot[c];
+    }
+  }
+  __syncthreads();
+  int32_t* o = offsets + (int64_t)bh * (C + 2);
+  for (int c = threadIdx.x; c <= C; c += kThreads) {
+    o[c] = offs[c];
+    for (int k = 0; k < nchunks; ++k) hist[(int64_t)k * (C + 1) + c] += offs[c];
+  }
+  if (threadIdx.x == 0) o[C + 1] = (int32_t)N;
+}
+
+__global__ void __launch_bounds__(kThreads)
+scatter_kernel(const int32_t* __restrict__ labels, int64_t N, int64_t nv, int C, int nchunks,
+               const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ perm) {
+  extern __shared__ int32_t sm[];  // base[C+1], lab_s[kThreads]
+  int32_t* base = sm;
+  int32_t* lab_s = sm + (C + 1);
+  const int bh = blockIdx.y, chunk = blockIdx.x;
+  const int32_t* hist = chunk_hist + ((int64_t)bh * nchunks + chunk) * (C + 1);
+  for (int c = threadIdx.x; c <= C; c += kThreads) base[c] = hist[c];
+  const int32_t* lab = labels + (int64_t)bh * nv;
+  int32_t* out = perm + (int64_t)bh * N;
+  const int64_t lo = (int64_t)chunk * kSortChunk;
+  for (int sub = 0; sub < kSortChunk / kThreads; ++sub) {
+    const int64_t i = lo + (int64_t)sub * kThreads + threadIdx.x;
+    const bool valid = i < N;
+    const int my = valid ? token_label(lab, i, nv, C) : -1;
+    __syncthreads();  // previous round's base updates and lab_s reads are done
+    lab_s[threadIdx.x] = my;
+    __syncthreads();
+    int rank = 0, total = 0;
+    for (int k = 0; k < kThreads; ++k) {
+      const int same = (lab_s[k] == my);
+      total += same;
+      rank += same & (k < (int)threadIdx.x);
+    }
+    int b = 0;
+    if (valid) {
+      b = base[my];
+      out[b + rank] = (int32_t)i;
+    }
+    __syncthreads();
+    if (valid && rank == total - 1) base[my] = b + total;
+    if (lo + (int64_t)(sub + 1) * kThreads >= N) break;
+  }
+}
+
+// dst[bh][p][:] = src[b,h,perm[p],:] in 16-byte units.
+__global__ void __launch_bounds__(kThreads)
+gather_rows_kernel(const uint4* __restrict__ src, Strides st_units, int H, const int32_t* __restrict__ perm,
+                   int64_t N, int row_units, uint4* __restrict__ dst) {
+  const int bh = blockIdx.y;
+  const int64_t u = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (u >= N * row_units) return;
+  const int64_t p = u / row_units;
+  const int v = (int)(u % row_units);
+  const int64_t row = perm[(int64_t)bh * N + p];
+  dst[((int64_t)bh * N + p) * row_units + v] = src[head_base(st_units, bh, H) + row * st_units.n + v];
+}
+
+// dst[b,h,perm[p],:] = src[bh][p][:]
+__global__ void __launch_bounds__(kThreads)
+scatter_rows_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ perm, int64_t N,
+                    int row_units, uint4* __restrict__ dst, Strides st_units, int H) {
+  const int bh = blockIdx.y;
+  const int64_t u = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (u >= N * row_units) return;
+  const int64_t p = u / row_units;
+  const int v = (int)(u % row_units);
+  const int64_t row = perm[(int64_t)bh * N + p];
+  dst[head_base(st_units, bh, H) + row * st_units.n + v] = src[((int64_t)bh * N + p) * row_units + v];
+}
+
+bool strides_ok(const int64_t st[3], size_t es, const void* p) {
+  if (!st) return false;
+  for (int i = 0; i < 3; ++i)
+    if (st[i] < 0 || (st[i] * (int64_t)es) % 16 != 0) return false;
+  return (reinterpret_cast<uintptr_t>(p) % 16) == 0;
+}
+
+}  // namespace
+
+int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C, int32_t* perm,
+                int32_t* offsets, int32_t* chunk_hist, hipStream_t s) {
+  const int nchunks = (int)sort_chunks(N);
+  const int64_t nv = N - n_tail;
+  dim3 grid(nchunks, BH);
+  hist_kernel<<<grid, kThreads, (C + 1) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks, chunk_hist);
+  SVGEAR_LAUNCH_CHECK();
+  scan_kernel<<<BH, kThreads, 2 * (C + 1) * sizeof(int32_t), s>>>(chunk_hist, N, C, nchunks, offsets);
+  SVGEAR_LAUNCH_CHECK();
+  scatter_kernel<<<grid, kThreads, (C + 1 + kThreads) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks,
+                                                                            chunk_hist, perm);
+  SVGEAR_LAUNCH_CHECK();
+  return SVGEAR_OK;
+}
+
+}  // namespace svgear
+
+using namespace svgear;
+
+extern "C" size_t svgear_permute_workspace(int B, int H, int64_t N, int C) {
+  if (B <= 0 || H <= 0 || N <= 0 || C <= 0) return 0;
+  return align_up((size_t)B * H * sort_chunks(N) * (C + 1) * sizeof(int32_t), 256);
+}
+
+extern "C" int svgear_permute(const int32_t* labels, int B, int H, int64_t N, int64_t n_tail, int C,
+                              int32_t* perm, int32_t* offsets, int n_tensors, const void* const* src,
+                              const int64_t (*sstride)[3], void* const* dst, svgear_dtype dt, int d,
+                              void* ws, size_t ws_bytes, void* stream) {
+  if (!labels || !perm || !offsets || B <= 0 || H <= 0 || N <= 0 || n_tail < 0 || n_tail >= N || C <= 0 ||
+      C > N - n_tail || N > INT32_MAX / 2 || n_tensors < 0 || n_tensors > 4 || C > 8192)
+    return SVGEAR_ERR_INVALID;
+  if (dt != SVGEAR_F32 && dt != SVGEAR_BF16) return SVGEAR_ERR_INVALID;
+  if (n_tensors > 0) {
+    if (!src || !dst || !sstride || (d != 64 && d != 128)) return SVGEAR_ERR_INVALID;
+    for (int k = 0; k < n_tensors; ++k)
+      if (!src[k] || !dst[k] || !strides_ok(sstride[k], esize(dt), src[k]) ||
+          reinterpret_cast<uintptr_t>(dst[k]) % 16)
+        return SVGEAR_ERR_INVALID;
+  }
+  if (!ws || ws_bytes < svgear_permute_workspace(B, H, N, C)) return SVGEAR_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int BH = B * H;
+  int rc = sort_labels(labels, BH, N, n_tail, C, perm, offsets, static_cast<int32_t*>(ws), s);
+  if (rc != SVGEAR_OK) return rc;
+  const int row_units = (int)(d * esize(dt) / 16);
+  const int upe = (int)(16 / esize(dt));  // elements per 16-byte unit
+  for (int k = 0; k < n_tensors; ++k) {
+    Strides st{sstride[k][0] / upe, sstride[k][1] / upe, sstride[k][2] / upe};
+    dim3 grid((unsigned)ceil_div(N * row_units, kThreads), BH);
+    gather_rows_kernel<<<grid, kThreads, 0, s>>>(static_cast<const uint4*>(src[k]), st, H, perm, N, row_units,
+                                                 static_cast<uint4*>(dst[k]));
+    SVGEAR_LAUNCH_CHECK();
+  }
+  return SVGEAR_OK;
+}
+
+extern "C" int svgear_unpermute(const void* op, const int32_t* perm, svgear_dtype dt, int B, int H, int64_t N,
+                                int d, void* o, const int64_t ostride[3], void* stream) {
+  if (!op || !perm || !o || B <= 0 || H <= 0 || N <= 0 || N > INT32_MAX / 2 || (d != 64 && d != 128))
+    return SVGEAR_ERR_INVALID;
+  if (dt != SVGEAR_F32 && dt != SVGEAR_BF16) return SVGEAR_ERR_INVALID;
+  if (!strides_ok(ostride, esize(dt), o) || reinterpret_cast<uintptr_t>(op) % 16) return SVGEAR_ERR_INVALID;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int row_units = (int)(d * esize(dt) / 16);
+  const int upe = (int)(16 / esize(dt));
+  Strides st{ostride[0] / upe, ostride[1] / upe, ostride[2] / upe};
+  dim3 grid((unsigned)ceil_div(N * row_units, kThreads), B * H);
+  scatter_rows_kernel<<<grid, kThreads, 0, s>>>(static_cast<const uint4*>(op), perm, N, row_units,
+                                                static_cast<uint4*>(o), st, H);
+  SVGEAR_LAUNCH_CHECK();
+  return SVGEAR_OK;
+}

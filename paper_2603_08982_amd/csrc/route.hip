@@ -1,0 +1,220 @@
+// Greedy error-to-cost routing under a cost budget, and the svgear_probe_route entry point.
+// Paper: "Error-Aware Routing" (blocks are taken in descending order of error-to-size ratio
+// until the budget is exhausted; the rest go to linear compensation); Experiments,
+// "Implementation" (per-query-cluster budgets).
+//
+// "Sort, prefix-sum the costs, cut at the budget" is done without a sort: the cut is the
+// first block, in (score desc, index asc) order, whose inclusive cumulative cost exceeds
+// the budget. Each block gets a unique 64-bit key that is monotone in that order; an
+// 8-pass, most-significant-byte-first radix descent over cost histograms finds the key K*
+// of the cut exactly (integer arithmetic only), and block (a,b) is routed iff key > K*.
+#include "common.h"
+
+namespace svgear {
+
+int run_probe(const float* qbar, const float* kbar, const float* vbar, const void* kp, const void* vp,
+              svgear_dtype dt, const int32_t* k_offsets, int BH, int64_t Nk, int d, int Cq, int Ck, float scale,
+              bool value_aware, float* scores, float* sbar, float* mrow, hipStream_t s);
+
+namespace {
+
+constexpr int kSelThreads = 1024;
+
+// Larger score -> larger key; among equal scores lower linear index -> larger key.
+__device__ __forceinline__ uint64_t block_key(float score, uint32_t idx) {
+  if (score != score) score = INFINITY;  // NaN ranks first
+  if (score == 0.f) score = 0.f;         // -0 and +0 tie
+  uint32_t u = __float_as_uint(score);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((uint64_t)u << 32) | (uint64_t)(0xFFFFFFFFu - idx);
+}
+
+// grid (nseg, BH): nseg = 1 (one budget per head) or Cq (one per query cluster).
+__global__ void __launch_bounds__(kSelThreads)
+select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_offsets,
+              const int32_t* __restrict__ k_offsets, int Cq, int Ck, int64_t budget, int per_row,
+              uint64_t* __restrict__ kstar) {
+  __shared__ unsigned long long hist[256];
+  __shared__ unsigned long long sh_prefix;
+  __shared__ long long sh_remaining;
+  __shared__ int sh_done;
+  const int seg = blockIdx.x, bh = blockIdx.y;
+  const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
+  const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
+  const float* sc = scores + (int64_t)bh * Cq * Ck;
+  const int64_t Nq = qo[Cq + 1], Nk = ko[Ck + 1];
+  const int64_t tq = qo[Cq + 1] - qo[Cq], tk = ko[Ck + 1] - ko[Ck];
+  const int a_lo = per_row ? seg : 0, a_hi = per_row ? seg + 1 : Cq;
+  const int64_t n_items = (int64_t)(a_hi - a_lo) * Ck;
+  if (threadIdx.x == 0) {
+    long long rem;
+    if (per_row) {
+      const int64_t qa = qo[seg + 1] - qo[seg];
+      rem = (budget * qa) / (Nq > 0 ? Nq : 1) - qa * tk;
+    } else {
+      rem = budget - (tq * Nk + (Nq - tq) * tk);
+    }
+    sh_remaining = rem > 0 ? rem : 0;
+    sh_prefix = 0ull;
+    sh_done = 0;
+  }
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+    for (int i = threadIdx.x; i < 256; i += kSelThreads) hist[i] = 0ull;
+    __syncthreads();
+    if (sh_done) break;
+    const unsigned long long prefix = sh_prefix;
+    for (int64_t it = threadIdx.x; it < n_items; it += kSelThreads) {
+      const int a = a_lo + (int)(it / Ck), b = (int)(it % Ck);
+      const int64_t cost = (int64_t)(qo[a + 1] - qo[a]) * (int64_t)(ko[b + 1] - ko[b]);
+      if (cost <= 0) continue;
+      const uint64_t key = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b));
+      if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
+      atomicAdd(&hist[(key >> shift) & 255u], (unsigned long long)cost);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      long long cum = 0;
+      const long long rem = sh_remaining;
+      int found = -1;
+      for (int dg = 255; dg >= 0; --dg) {
+        const long long h = (long long)hist[dg];
+        if (cum + h > rem) {
+          found = dg;
+          break;
+        }
+        cum += h;
+      }
+      if (found < 0) {  // everything fits (can only happen on the first pass)
+        sh_done = 1;
+        sh_prefix = 0ull;
+      } else {
+        sh_remaining = rem - cum;
+        sh_prefix = (prefix << 8) | (unsigned long long)found;
+      }
+    }
+    __syncthreads();
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) kstar[(int64_t)bh * (per_row ? Cq : 1) + seg] = sh_prefix;
+}
+
+// grid (BH). Builds the bit mask, the CSR lists and the routed cost from K*.
+__global__ void __launch_bounds__(256)
+build_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_offsets,
+             const int32_t* __restrict__ k_offsets, int Cq, int Ck, int per_row,
+             const uint64_t* __restrict__ kstar, uint32_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
+             int32_t* __restrict__ col_idx, int64_t* __restrict__ routed_cost) {
+  extern __shared__ int32_t rowcnt[];  // Cq+2
+  __shared__ unsigned long long cost_sum;
+  const int bh = blockIdx.x;
+  const int R = Cq + 1, Cc = Ck + 1, W = (Cc + 31) / 32;
+  const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
+  const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
+  const float* sc = scores + (int64_t)bh * Cq * Ck;
+  uint32_t* mb = mask_bits + (int64_t)bh * R * W;
+  for (int a = threadIdx.x; a < R + 1; a += 256) rowcnt[a] = 0;
+  if (threadIdx.x == 0) cost_sum = 0ull;
+  __syncthreads();
+  long long my_cost = 0;
+  for (int it = threadIdx.x; it < R * W; it += 256) {
+    const int a = it / W, w = it % W;
+    const int64_t qa = qo[a + 1] - qo[a];
+    uint32_t bits = 0;
+    if (qa > 0) {
+      const uint64_t ks = (a < Cq) ? kstar[(int64_t)bh * (per_row ? Cq : 1) + (per_row ? a : 0)] : 0ull;
+      for (int j = 0; j < 32; ++j) {
+        const int b = w * 32 + j;
+        if (b >= Cc) break;
+        const int64_t kb = ko[b + 1] - ko[b];
+        if (kb <= 0) continue;
+        bool on = (a == Cq) || (b == Ck);
+        if (!on) on = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b)) > ks;
+        if (on) {
+          bits |= 1u << j;
+          my_cost += qa * kb;
+        }
+      }
+    }
+    mb[it] = bits;
+    if (bits) atomicAdd(&rowcnt[a], __popc(bits));
+  }
+  atomicAdd(&cost_sum, (unsigned long long)my_cost);
+  __syncthreads();
+  int32_t* rp = row_ptr + (int64_t)bh * (R + 1);
+  if (threadIdx.x == 0) {
+    int32_t run = 0;
+    for (int a = 0; a < R; ++a) {
+      const int32_t c = rowcnt[a];
+      rowcnt[a] = run;
+      rp[a] = run;
+      run += c;
+    }
+    rp[R] = run;
+    routed_cost[bh] = (int64_t)cost_sum;
+  }
+  __syncthreads();
+  int32_t* ci = col_idx + (int64_t)bh * R * Cc;
+  for (int a = threadIdx.x; a < R; a += 256) {
+    int32_t pos = rowcnt[a];
+    for (int w = 0; w < W; ++w) {
+      uint32_t bits = mb[a * W + w];
+      while (bits) {
+        const int j = __ffs(bits) - 1;
+        bits &= bits - 1;
+        ci[pos++] = w * 32 + j;
+      }
+    }
+  }
+}
+
+}  // namespace
+}  // namespace svgear
+
+using namespace svgear;
+
+extern "C" size_t svgear_probe_route_workspace(int B, int H, int64_t Nk, int d, int Cq, int Ck) {
+  (void)Nk; (void)d;
+  if (B <= 0 || H <= 0 || Cq <= 0 || Ck <= 0) return 0;
+  const size_t BH = (size_t)B * H;
+  return align_up(BH * Cq * Ck * 4, 256) + align_up(BH * Cq * 4, 256) + align_up(BH * (Cq + 1) * 8, 256);
+}
+
+extern "C" int svgear_probe_route(const float* qbar, const float* kbar, const float* vbar, const void* kp,
+                                  const void* vp, svgear_dtype dt, const int32_t* q_offsets,
+                                  const int32_t* k_offsets, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
+                                  int Ck, int64_t budget_cost, float scale, unsigned flags, float* scores,
+                                  uint32_t* mask_bits, int32_t* row_ptr, int32_t* col_idx, int64_t* routed_cost,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  const bool given = flags & SVGEAR_USE_GIVEN_SCORES;
+  if (!q_offsets || !k_offsets || !scores || !mask_bits || !row_ptr || !col_idx || !routed_cost || B <= 0 ||
+      H <= 0 || Nq <= 0 || Nk <= 0 || Cq <= 0 || Ck <= 0 || Cq > 8192 || Ck > 8192 || budget_cost < 0 ||
+      Nq > INT32_MAX / 2 || Nk > INT32_MAX / 2 || (flags & ~7u) || (int64_t)(Cq + 1) * (Ck + 1) > INT32_MAX / 2)
+    return SVGEAR_ERR_INVALID;
+  if (!given) {
+    if (!qbar || !kbar || !vbar || !kp || !vp || (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) ||
+        reinterpret_cast<uintptr_t>(kp) % 16 || reinterpret_cast<uintptr_t>(vp) % 16 ||
+        reinterpret_cast<uintptr_t>(qbar) % 16 || reinterpret_cast<uintptr_t>(kbar) % 16)
+      return SVGEAR_ERR_INVALID;
+  }
+  if (!ws || ws_bytes < svgear_probe_route_workspace(B, H, Nk, d, Cq, Ck)) return SVGEAR_ERR_WORKSPACE;
+  const int BH = B * H;
+  Workspace w(ws, ws_bytes);
+  float* sbar = w.take<float>((size_t)BH * Cq * Ck);
+  float* mrow = w.take<float>((size_t)BH * Cq);
+  uint64_t* kstar = w.take<uint64_t>((size_t)BH * (Cq + 1));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!given) {
+    int rc = run_probe(qbar, kbar, vbar, kp, vp, dt, k_offsets, BH, Nk, d, Cq, Ck, scale,
+                       !(flags & SVGEAR_PROBE_PLAIN), scores, sbar, mrow, s);
+    if (rc != SVGEAR_OK) return rc;
+  }
+  const int per_row = (flags & SVGEAR_ROUTE_PER_ROW) ? 1 : 0;
+  select_kernel<<<dim3(per_row ? Cq : 1, BH), kSelThreads, 0, s>>>(scores, q_offsets, k_offsets, Cq, Ck, budget_cost,
+                                                                  per_row, kstar);
+  SVGEAR_LAUNCH_CHECK();
+  build_kernel<<<BH, 256, (Cq + 2) * sizeof(int32_t), s>>>(scores, q_offsets, k_offsets, Cq, Ck, per_row, kstar,
+                                                          mask_bits, row_ptr, col_idx, routed_cost);
+  SVGEAR_LAUNCH_CHECK();
+  return SVGEAR_OK;
+}

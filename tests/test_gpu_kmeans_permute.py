@@ -1,0 +1,149 @@
+"""GPU parity: svgear_kmeans / svgear_permute / svgear_unpermute against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_08982_amd as sv
+from oracle import svgear_oracle as orc
+from workloads import get_workload, make_qkv
+from helpers import dev, to_np, init_centroids
+
+pytestmark = pytest.mark.gpu
+
+
+def _lockstep(X, C, iters, n_tail=0, seed=0, tensor_id=0, X2=None):
+    """Each iteration: GPU starts from the oracle's centroids; labels must be bit-exact and
+    the updated centroids within fp32 summation tolerance."""
+    B, H, N, d = X.shape
+    cent0 = init_centroids(X, C, seed, tensor_id, n_tail)
+    oc = [[to_np(cent0[b, h]).copy() for h in range(H)] for b in range(B)]
+    for it in range(iters):
+        g = torch.stack([torch.stack([torch.from_numpy(oc[b][h]) for h in range(H)]) for b in range(B)]).to(X.device)
+        labels, counts, c2 = sv.kmeans(X, g, 1, n_tail, x2=X2)
+        torch.cuda.synchronize()
+        for b in range(B):
+            for h in range(H):
+                x = to_np(X[b, h])[: N - n_tail]
+                x2 = None if X2 is None else to_np(X2[b, h])[: N - n_tail]
+                c_new, lab, cnt, c2_ref = orc.kmeans(x, oc[b][h], 1, X2=x2)
+                assert np.array_equal(to_np(labels[b, h]), lab), f"labels differ it={it} head={b},{h}"
+                assert np.array_equal(to_np(counts[b, h]), cnt)
+                tol = 1e-5 * np.maximum(1.0, np.abs(c_new))
+                assert np.all(np.abs(to_np(g[b, h]) - c_new) <= tol)
+                if X2 is not None:
+                    ne = cnt > 0
+                    assert np.all(np.abs(to_np(c2[b, h])[ne] - c2_ref[ne]) <= 1e-5 * np.maximum(1.0, np.abs(c2_ref[ne])))
+                oc[b][h] = c_new
+
+
+def test_kmeans_lockstep_tiny_fp32():
+    wl = get_workload("tiny")
+    Q, K, V = make_qkv(wl, dev())
+    _lockstep(Q, wl.Cq, 4, tensor_id=0)
+    _lockstep(K, wl.Ck, 3, tensor_id=1, X2=V)
+
+
+def test_kmeans_lockstep_video_bf16_with_tail():
+    wl = get_workload("mini_video_tail")
+    Q, K, V = make_qkv(wl, dev())
+    _lockstep(K, wl.Ck, 3, n_tail=wl.n_tail, seed=wl.seed, tensor_id=1, X2=V)
+    wl = get_workload("mini_video")
+    Q, K, V = make_qkv(wl, dev())
+    _lockstep(Q, wl.Cq, 2, seed=wl.seed, tensor_id=0)
+
+
+def test_kmeans_free_running_matches_oracle():
+    wl = get_workload("tiny")
+    Q, K, V = make_qkv(wl, dev())
+    cent = init_centroids(K, wl.Ck, 0, 1)
+    init = to_np(cent[0, 0]).copy()
+    labels, counts, vbar = sv.kmeans(K, cent, wl.iters, x2=V)
+    torch.cuda.synchronize()
+    c_ref, l_ref, n_ref, v_ref = orc.kmeans(to_np(K[0, 0]), init, wl.iters, X2=to_np(V[0, 0]))
+    lab = to_np(labels[0, 0])
+    agree = (lab == l_ref).mean()
+    assert agree > 0.999
+    j_gpu = orc.inertia(to_np(K[0, 0]), to_np(cent[0, 0]), lab)
+    j_ref = orc.inertia(to_np(K[0, 0]), c_ref, l_ref)
+    assert abs(j_gpu - j_ref) <= 1e-4 * j_ref
+    if agree == 1.0:
+        assert np.allclose(to_np(cent[0, 0]), c_ref, rtol=0, atol=1e-5 * max(1, np.abs(c_ref).max()))
+        assert np.array_equal(to_np(counts[0, 0]), n_ref)
+
+
+def test_kmeans_edge_cases():
+    g = torch.Generator(device="cpu").manual_seed(0)
+    # C = 1, N not a multiple of any tile, d = 128 fp32
+    X = torch.randn(1, 1, 1037, 128, generator=g).to(dev())
+    cent = X[:, :, :1].clone().float()
+    labels, counts, _ = sv.kmeans(X, cent, 2)
+    torch.cuda.synchronize()
+    assert int(labels.abs().sum()) == 0 and int(counts[0, 0, 0]) == 1037
+    assert np.allclose(to_np(cent[0, 0, 0]), to_np(X[0, 0]).astype(np.float64).mean(0), atol=1e-5)
+    # duplicate initial centroids: ties go to the lowest index, the duplicate stays empty
+    # and keeps its centroid
+    X = torch.randn(1, 2, 300, 64, generator=g).to(dev())
+    init = X[:, :, [0, 5, 5, 9]].clone().float()
+    keep = to_np(init[0, 1, 2]).copy()
+    c = init.clone()
+    labels, counts, _ = sv.kmeans(X, c, 1)
+    torch.cuda.synchronize()
+    assert int((labels == 2).sum()) == 0
+    assert int(counts[0, 1, 2]) == 0 and np.array_equal(to_np(c[0, 1, 2]), keep)
+    for h in range(2):
+        _, l_ref, n_ref, _ = orc.kmeans(to_np(X[0, h]), to_np(init[0, h]), 1)
+        assert np.array_equal(to_np(labels[0, h]), l_ref)
+    # strided [B, N, H, d] storage viewed as [B, H, N, d]
+    base = torch.randn(2, 150, 3, 64, generator=g).to(dev())
+    Xs = base.permute(0, 2, 1, 3)
+    assert not Xs.is_contiguous()
+    init = Xs[:, :, :5].contiguous().float()
+    c = init.clone()
+    labels, counts, _ = sv.kmeans(Xs, c, 2)
+    torch.cuda.synchronize()
+    for b in range(2):
+        for h in range(3):
+            c_ref, l_ref, n_ref, _ = orc.kmeans(to_np(Xs[b, h]), to_np(init[b, h]), 2)
+            assert np.array_equal(to_np(labels[b, h]), l_ref)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_video_tail"])
+def test_permute_bit_exact_and_roundtrip(name):
+    wl = get_workload(name)
+    Q, K, V = make_qkv(wl, dev())
+    B, H, N, d = Q.shape
+    nv = N - wl.n_tail
+    g = torch.Generator(device="cpu").manual_seed(7)
+    labels = torch.randint(0, wl.Ck, (B, H, nv), generator=g, dtype=torch.int32)
+    labels[labels == 3] = 4  # an empty cluster
+    labels = labels.to(dev())
+    perm, off, (Kp, Vp) = sv.permute(labels, wl.Ck, [K, V], wl.n_tail)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for h in range(H):
+            p_ref, o_ref = orc.permute(to_np(labels[b, h]), wl.Ck, wl.n_tail)
+            assert np.array_equal(to_np(perm[b, h]), p_ref)
+            assert np.array_equal(to_np(off[b, h]), o_ref)
+            assert torch.equal(Kp[b, h].cpu(), K[b, h].cpu()[torch.from_numpy(p_ref).long()])
+            assert torch.equal(Vp[b, h].cpu(), V[b, h].cpu()[torch.from_numpy(p_ref).long()])
+    back = sv.unpermute(Kp, perm)
+    torch.cuda.synchronize()
+    assert torch.equal(back, K)
+    # strided output: write into a [B, N, H, d] buffer
+    buf = torch.zeros(B, N, H, d, dtype=K.dtype, device=dev())
+    sv.unpermute(Vp, perm, out=buf.permute(0, 2, 1, 3))
+    torch.cuda.synchronize()
+    assert torch.equal(buf.permute(0, 2, 1, 3), V)
+
+
+def test_permute_large_chunks_and_many_clusters():
+    # several sort chunks per head (N > 2048), sizes straddling chunk boundaries
+    g = torch.Generator(device="cpu").manual_seed(11)
+    N, C = 2048 * 3 + 123, 700
+    labels = torch.randint(0, C, (1, 2, N), generator=g, dtype=torch.int32).to(dev())
+    perm, off, _ = sv.permute(labels, C)
+    torch.cuda.synchronize()
+    for h in range(2):
+        p_ref, o_ref = orc.permute(to_np(labels[0, h]), C, 0)
+        assert np.array_equal(to_np(perm[0, h]), p_ref)
+        assert np.array_equal(to_np(off[0, h]), o_ref)
