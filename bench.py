@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the SVG-EAR attention hot path on one MI355X.
+
+A "step" is one pass of the whole hot path (k-means of Q and K, permutation, probe + route,
+fused sparse attention with compensation, un-permutation) over one synthetic attention layer
+with Q/K/V already resident in HBM. The default workload is the Wan2.2-shaped layer
+(H=40, N=75600, d=128, bf16, C_q=100, C_k=500, 10 cold k-means iterations, 25% routed budget).
+
+Prints ONE JSON line with the whole-layer figure (dense-equivalent TFLOP/s = 4 H N^2 d / t),
+per-stage times, the roofline of the dominant kernel (fused attention, bf16 MFMA), the rel-L2
+error of sampled output rows against the CPU oracle, the dense brackets, and the CPU oracle
+timed on a bounded sample on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+import torch  # noqa: E402
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="wan", help="wan | hunyuan | tiny | mini_video ...")
+    ap.add_argument("--heads", type=int, default=0, help="override head count (debug)")
+    ap.add_argument("--rho", type=float, default=-1.0, help="override routed budget fraction")
+    ap.add_argument("--iters", type=int, default=-1, help="override k-means iterations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense brackets")
+    ap.add_argument("--sample-rows", type=int, default=96, help="output rows checked against the oracle")
+    return ap.parse_args()
+
+
+def bits_to_mask(bits: np.ndarray, Ck: int) -> np.ndarray:
+    bits = bits.astype(np.uint32)
+    R, W = bits.shape
+    out = np.zeros((R, W * 32), dtype=bool)
+    for j in range(32):
+        out[:, j::32] = (bits >> np.uint32(j)) & 1
+    return out[:, : Ck + 1]
+
+
+class StageTimer:
+    """HIP events on torch's current stream (the stream every library call is enqueued on)."""
+
+    def __init__(self):
+        self.marks = []
+
+    def mark(self, name):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        self.marks.append((name, ev))
+
+    def stages_ms(self):
+        out = {}
+        for (n0, e0), (n1, e1) in zip(self.marks[:-1], self.marks[1:]):
+            out[n1] = out.get(n1, 0.0) + e0.elapsed_time(e1)
+        return out
+
+
+def run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget, timer=None):
+    """One pass of the whole path (cold k-means start: centroids reset from the seeded init)."""
+    cq.copy_(cq0)
+    ck.copy_(ck0)
+    scale = float(wl.d) ** -0.5
+    if timer: timer.mark("start")
+    lab_q, qcnt, _ = sv.kmeans(Q, cq, wl.iters, wl.n_tail)
+    lab_k, kcnt, vbar = sv.kmeans(K, ck, wl.iters, wl.n_tail, x2=V)
+    if timer: timer.mark("kmeans")
+    perm_q, qoff, (Qp,) = sv.permute(lab_q, wl.Cq, [Q], wl.n_tail)
+    perm_k, koff, (Kp, Vp) = sv.permute(lab_k, wl.Ck, [K, V], wl.n_tail)
+    if timer: timer.mark("permute")
+    r = sv.probe_route(cq, ck, vbar, Kp, Vp, qoff, koff, budget, scale)
+    if timer: timer.mark("probe_route")
+    Op, _ = sv.sparse_attn_comp(Qp, Kp, Vp, ck, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
+    if timer: timer.mark("attention")
+    O = sv.unpermute(Op, perm_q)
+    if timer: timer.mark("unpermute")
+    r.update(O=O, Op=Op, Qp=Qp, Kp=Kp, Vp=Vp, qoff=qoff, koff=koff, perm_q=perm_q, perm_k=perm_k, vbar=vbar,
+             lab_q=lab_q, lab_k=lab_k)
+    return r
+
+
+def oracle_rows_rel_l2(orc, wl, r, cq, ck, head, n_rows, rng):
+    """rel-L2 of sampled output rows of one head against the oracle's literal evaluation of
+    Eq. (1)+(6) on the GPU's own clustering and mask."""
+    f = lambda t: t.float().cpu().numpy()
+    qoff = r["qoff"][0, head].cpu().numpy()
+    koff = r["koff"][0, head].cpu().numpy()
+    rows = np.sort(rng.choice(wl.N, size=min(n_rows, wl.N), replace=False))
+    lq_all = np.repeat(np.arange(wl.Cq + 1), np.diff(qoff))
+    lk = np.repeat(np.arange(wl.Ck + 1), np.diff(koff))
+    mask = bits_to_mask(r["mask_bits"][0, head].cpu().numpy(), wl.Ck)
+    kb = np.concatenate([f(ck[0, head]), np.zeros((1, wl.d), np.float32)])
+    vb = np.concatenate([f(r["vbar"][0, head]), np.zeros((1, wl.d), np.float32)])
+    Qs = f(r["Qp"][0, head][torch.from_numpy(rows).to(r["Qp"].device)])
+    ref = orc.attention_comp(Qs, f(r["Kp"][0, head]), f(r["Vp"][0, head]), lq_all[rows], lk, kb, vb, mask,
+                             orc.scale_of(wl.d), row_chunk=32)
+    got = f(r["Op"][0, head][torch.from_numpy(rows).to(r["Op"].device)])
+    return float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+
+
+def cpu_baseline(orc, wl, Q, K, V, cq0, ck0, budget, n_rows=48):
+    """The oracle as it stands on this machine's host cores, on a bounded sample of the workload:
+    head 0, ONE k-means iteration of Q and of K (scaled by the iteration count), the probe,
+    the router, and the attention definition on `n_rows` query rows (scaled to all rows);
+    the head time is scaled by the head count. Extrapolated, labelled as such."""
+    f = lambda t: t.float().cpu().numpy()
+    q, k, v = f(Q[0, 0]), f(K[0, 0]), f(V[0, 0])
+    nv = wl.N - wl.n_tail
+    t0 = time.perf_counter()
+    qbar, lab_q, qcnt, _ = orc.kmeans(q[:nv], f(cq0[0, 0]), 1)
+    kbar, lab_k, kcnt, vbar = orc.kmeans(k[:nv], f(ck0[0, 0]), 1, X2=v[:nv])
+    t_km = (time.perf_counter() - t0) * wl.iters
+    t0 = time.perf_counter()
+    perm_q, qoff = orc.permute(lab_q, wl.Cq, wl.n_tail)
+    perm_k, koff = orc.permute(lab_k, wl.Ck, wl.n_tail)
+    Qp, Kp, Vp = q[perm_q], k[perm_k], v[perm_k]
+    t_perm = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    E, scores, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, koff, orc.scale_of(wl.d))
+    mask, rp, ci, cost = orc.route(scores, qcnt, kcnt, budget, n_tail_q=wl.n_tail, n_tail_k=wl.n_tail)
+    t_pr = time.perf_counter() - t0
+    lq = np.repeat(np.arange(wl.Cq + 1), np.diff(qoff))
+    lk = np.repeat(np.arange(wl.Ck + 1), np.diff(koff))
+    fm = np.zeros((wl.Cq + 1, wl.Ck + 1), bool)
+    fm[: mask.shape[0], : mask.shape[1]] = mask
+    kb = np.concatenate([kbar, np.zeros((1, wl.d), np.float32)])
+    vb = np.concatenate([vbar, np.zeros((1, wl.d), np.float32)])
+    rows = np.linspace(0, wl.N - 1, n_rows).astype(np.int64)
+    t0 = time.perf_counter()
+    orc.attention_comp(Qp[rows], Kp, Vp, lq[rows], lk, kb, vb, fm, orc.scale_of(wl.d), row_chunk=16)
+    t_att = (time.perf_counter() - t0) * (wl.N / n_rows)
+    t_head = t_km + t_perm + t_pr + t_att
+    t_layer = t_head * wl.H * wl.B
+    dense_flops = 4.0 * wl.B * wl.H * float(wl.N) ** 2 * wl.d
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        blas_threads = 1
+    return {
+        "value": dense_flops / t_layer / 1e12, "unit": "TFLOP/s", "cores": max(orc.host_threads(), blas_threads),
+        "kind": "oracle",
+        "sample": (f"head 0 of {wl.H}: 1 of {wl.iters} k-means iterations (Q and K), permute, probe, route in full; "
+                   f"attention on {n_rows} of {wl.N} query rows; scaled linearly to the layer (extrapolated)"),
+        "s_per_layer_extrapolated": t_layer,
+        "stage_s_per_head": {"kmeans": t_km, "permute": t_perm, "probe_route": t_pr, "attention": t_att},
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (heads are independent and would shard over GPUs with no "
+              "communication inside the layer, but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
+        sys.exit(2)
+    import paper_2603_08982_amd as sv
+    from workloads import get_workload, make_qkv, kmeans_init_indices, budget_pairs
+
+    sv.load_library()
+    dev = torch.device("cuda:0")
+    wl = get_workload(args.workload)
+    if args.heads > 0: wl = wl.with_(H=args.heads)
+    if args.rho >= 0: wl = wl.with_(rho=args.rho)
+    if args.iters > 0: wl = wl.with_(iters=args.iters)
+    budget = budget_pairs(wl.rho, wl.N, wl.N)
+
+    Q, K, V = make_qkv(wl, dev)
+    nv = wl.N - wl.n_tail
+    cq0 = torch.empty(wl.B, wl.H, wl.Cq, wl.d, device=dev)
+    ck0 = torch.empty(wl.B, wl.H, wl.Ck, wl.d, device=dev)
+    for b in range(wl.B):
+        for h in range(wl.H):
+            iq = torch.from_numpy(kmeans_init_indices(wl.seed, b * wl.H + h, 0, nv, wl.Cq)).to(dev)
+            ik = torch.from_numpy(kmeans_init_indices(wl.seed, b * wl.H + h, 1, nv, wl.Ck)).to(dev)
+            cq0[b, h] = Q[b, h][iq].float()
+            ck0[b, h] = K[b, h][ik].float()
+    cq, ck = cq0.clone(), ck0.clone()
+
+    for _ in range(args.warmup):
+        run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget)
+    torch.cuda.synchronize()
+    timers = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tm = StageTimer()
+        r = run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget, tm)
+        timers.append(tm)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    stages = {}
+    for tm in timers:
+        for k, v in tm.stages_ms().items():
+            stages[k] = stages.get(k, 0.0) + v / args.steps
+
+    dense_flops = 4.0 * wl.B * wl.H * float(wl.N) ** 2 * wl.d
+    value = dense_flops / (ms_per_step * 1e-3) / 1e12
+
+    # algorithmic flops of the fused attention kernel: routed pairs + one pseudo-key per skipped cluster
+    routed_pairs = float(r["routed_cost"].sum().item())
+    mask_all = r["mask_bits"].cpu().numpy()
+    qoff_all = r["qoff"].cpu().numpy()
+    koff_all = r["koff"].cpu().numpy()
+    comp_pairs = 0.0
+    for b in range(wl.B):
+        for h in range(wl.H):
+            m = bits_to_mask(mask_all[b, h], wl.Ck)[: wl.Cq, : wl.Ck]
+            qs = np.diff(qoff_all[b, h])[: wl.Cq]
+            ks = np.diff(koff_all[b, h])[: wl.Ck]
+            comp_pairs += float((qs[:, None] * ((~m) & (ks[None, :] > 0))).sum())
+    attn_flops = 4.0 * wl.d * (routed_pairs + comp_pairs)
+    attn_ms = stages["attention"]
+    achieved = attn_flops / (attn_ms * 1e-3) / 1e12
+    density = routed_pairs / (wl.B * wl.H * float(wl.N) ** 2)
+
+    from oracle import svgear_oracle as orc
+    rng = np.random.default_rng(0)
+    rel = max(oracle_rows_rel_l2(orc, wl, r, cq, ck, h, args.sample_rows, rng) for h in sorted({0, wl.H - 1}))
+
+    out = {
+        "metric": "dense-equivalent TFLOP/s of one attention layer, whole hot path "
+                  "(k-means + permute + probe/route + fused sparse attention with compensation + unpermute)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} H={wl.H} N={wl.N} (tail {wl.n_tail}) d={wl.d} Cq={wl.Cq} "
+                               f"Ck={wl.Ck} kmeans_iters={wl.iters} (cold start) rho={wl.rho}",
+                   "budget_pairs_per_head": budget},
+        "stages_ms": stages,
+        "achieved_density": density,
+        "rel_l2_vs_oracle_sampled_rows": rel,
+        "attention_stage": {"ms": attn_ms, "dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12},
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if wl.dtype == "bf16" else "attn_f32_kernel",
+                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_launch": attn_flops},
+    }
+
+    if not args.no_dense and wl.dtype == "bf16":
+        # dense brackets on the same tensors: this library at 100% budget, and torch SDPA
+        full = sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], wl.N * wl.N,
+                              float(wl.d) ** -0.5, flags=sv.USE_GIVEN_SCORES, scores=r["scores"])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"], full["mask_bits"],
+                            full["row_ptr"], full["col_idx"], float(wl.d) ** -0.5)
+        e1.record()
+        torch.cuda.synchronize()
+        own_ms = e0.elapsed_time(e1)
+        sd = {}
+        try:
+            torch.nn.functional.scaled_dot_product_attention(Q[:, :2], K[:, :2], V[:, :2])
+            torch.cuda.synchronize()
+            e0.record()
+            torch.nn.functional.scaled_dot_product_attention(Q, K, V)
+            e1.record()
+            torch.cuda.synchronize()
+            sd = {"torch_sdpa_ms": e0.elapsed_time(e1),
+                  "torch_sdpa_tflops": dense_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12}
+        except Exception as ex:  # noqa: BLE001
+            sd = {"torch_sdpa_error": str(ex)[:200]}
+        out["dense_bracket"] = {"own_kernel_all_routed_ms": own_ms,
+                                "own_kernel_all_routed_tflops": dense_flops / (own_ms * 1e-3) / 1e12, **sd}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(orc, wl, Q, K, V, cq0, ck0, budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
