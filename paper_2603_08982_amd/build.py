@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsvgear.so")
-SOURCES = ["api.hip", "permute.hip", "kmeans.hip", "probe.hip", "route.hip", "attention.hip"]
+SOURCES = ["api.hip", "permute.hip", "kmeans.hip", "probe.hip", "route.hip", "attention.hip", "attention_bf16.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

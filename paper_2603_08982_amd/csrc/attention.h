@@ -1,0 +1,46 @@
+// Shared declarations of the fused attention kernels (internal).
+#pragma once
+#include "common.h"
+
+namespace svgear {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int BN = 64;  // keys per tile
+
+struct AttnArgs {
+  const void* qp;
+  const void* kp;
+  const void* vp;
+  const float* kbar;
+  const float* vbar;
+  const bf16_t* kbar16;
+  const bf16_t* vbar16;
+  const int32_t* q_offsets;
+  const int32_t* k_offsets;
+  const uint32_t* mask_bits;
+  const int32_t* row_ptr;
+  const int32_t* col_idx;
+  const int32_t* tile_a;
+  const int32_t* tile_row0;
+  const int32_t* n_tiles;
+  int64_t Nq, Nk;
+  int BH, Cq, Ck, max_tiles;
+  float scale;
+  void* op;
+  float* lse;
+};
+
+__device__ __forceinline__ bool mask_bit(const uint32_t* mrow, int b) { return (mrow[b >> 5] >> (b & 31)) & 1u; }
+
+
+// Rows of queries per workgroup tile of the bf16 kernels.
+constexpr int kBf16Waves = 4;
+constexpr int kBf16BM = 32 * kBf16Waves;
+
+// LDS bytes the bf16 kernel needs for head dimension d and Ck key clusters.
+size_t attn_bf16_lds_bytes(int d, int Ck);
+// Launches the bf16 MFMA kernel over `total` (multiple of 8) workgroups.
+int launch_attn_bf16(const AttnArgs& a, int d, unsigned total, hipStream_t s);
+
+}  // namespace svgear
