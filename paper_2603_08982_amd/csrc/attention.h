@@ -34,9 +34,10 @@ struct AttnArgs {
 __device__ __forceinline__ bool mask_bit(const uint32_t* mrow, int b) { return (mrow[b >> 5] >> (b & 31)) & 1u; }
 
 
-// Rows of queries per workgroup tile of the bf16 kernels.
+// Waves per workgroup of the generic bf16 kernel (32 query rows per wave).
 constexpr int kBf16Waves = 4;
-constexpr int kBf16BM = 32 * kBf16Waves;
+// Query rows per workgroup tile of the bf16 kernel used for head dimension d.
+int attn_bf16_bm(int d);
 
 // LDS bytes the bf16 kernel needs for head dimension d and Ck key clusters.
 size_t attn_bf16_lds_bytes(int d, int Ck);

@@ -201,7 +201,7 @@ attn_f32_kernel(AttnArgs p) {
 
 using namespace svgear;
 
-static int attn_bm(svgear_dtype dt) { return dt == SVGEAR_F32 ? 64 : 32 * kBf16Waves; }
+static int attn_bm(svgear_dtype dt, int d) { return dt == SVGEAR_F32 ? 64 : attn_bf16_bm(d); }
 
 extern "C" size_t svgear_sparse_attn_comp_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq, int Ck) {
   (void)Nk;
@@ -230,7 +230,7 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
   if ((int64_t)BH * ((int64_t)ceil_div(Nq, 64) + Cq + 1) > INT32_MAX / 2) return SVGEAR_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   Workspace w(ws, ws_bytes);
-  const int BM = attn_bm(dt);
+  const int BM = attn_bm(dt, d);
   const int max_tiles = (int)(ceil_div(Nq, BM) + Cq + 1);
   const size_t cap = (size_t)ceil_div(Nq, 64) + Cq + 1;
   int32_t* tile_a = w.take<int32_t>((size_t)BH * cap);

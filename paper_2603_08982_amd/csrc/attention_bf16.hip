@@ -2,6 +2,8 @@
 // Paper: Eq. (1), Eq. (6), Algorithm 2 (see attention.hip for the decomposition).
 #include "attention.h"
 
+#include <type_traits>
+
 namespace svgear {
 namespace {
 
@@ -361,6 +363,17 @@ attn_bf16_kernel(AttnArgs p) {
 // Bank conflicts are avoided by XOR-swizzling the 16-byte chunk index inside each 256 B
 // row (K: chunk ^ (row % 16); V: chunk ^ 4*(row % 4)); the swizzle is applied on the
 // global side of the copy (a lane picks which global chunk lands in its LDS slot).
+constexpr float kLazyRescale = 8.0f;  // log2 headroom before the running maximum is refreshed
+
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+// acc + lo(p) + hi(p) for a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
+__device__ __forceinline__ float dot2_ones(uint32_t pair, float acc) {
+  union { uint32_t u; bf16x2v b; } x, one;
+  x.u = pair;
+  one.u = 0x3f803f80u;
+  return __builtin_amdgcn_fdot2_f32_bf16(x.b, one.b, acc, false);
+}
+
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16* lds_v4i16_ptr;
 
@@ -373,30 +386,53 @@ __device__ __forceinline__ bf16x8 tr_pair(const unsigned char* lds_base, int off
   return c.v;
 }
 
-static inline size_t lds_bytes_d128(int Ck) {
-  const size_t kv = 2 * 2 * (size_t)BN * 128 * 2;  // K and V, two buffers each
-  const size_t lw = (size_t)align_up(Ck, 64) * 4;
-  const size_t seg = (size_t)(2 * (Ck + 1) + 1) * 4;
-  return kv + 2 * BN * 4 + lw + align_up(seg, 16);
+// 16 bytes per lane from global memory straight into LDS: the wave's 64 lanes fill 1 KB
+// starting at LDS byte address `lds_addr` (wave-uniform), lane l at lds_addr + 16 l.
+// Written as inline assembly so that the compiler does not treat every later LDS read as
+// dependent on the copy (it would drain the copies before the first read of each tile);
+// completion is tracked by hand with vmcnt.
+__device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)(p);
 }
 
-template <int NW>
-__global__ void __launch_bounds__(64 * NW, 2)
+static inline size_t lds_bytes_d128(int Ck, int stages) {
+  const size_t kv = (size_t)stages * 2 * BN * 128 * 2;  // K and V, `stages` buffers each
+  const size_t lw = (size_t)align_up(Ck, 64) * 4;
+  const size_t seg = (size_t)(2 * (Ck + 1) + 1) * 4;
+  return kv + (size_t)(stages + 2) * BN * 4 + lw + align_up(seg, 16);
+}
+
+// vmcnt(n) with expcnt and lgkmcnt left unconstrained (gfx9 s_waitcnt encoding)
+#define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// NW waves of 32 query rows; NSTAGE K/V tile buffers (tile t+NSTAGE-1 is in flight while
+// tile t is computed).
+template <int NW, int NSTAGE>
+__global__ void __launch_bounds__(64 * NW, 8 / NW)
 attn_bf16_d128_kernel(AttnArgs p) {
   constexpr int D = 128;
   constexpr int NT = 64 * NW;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
-  constexpr int TILE_BYTES = BN * D * 2;       // 16 KB
+  constexpr int TILE_BYTES = BN * D * 2;            // 16 KB
   constexpr int INST_PER_TILE = TILE_BYTES / 1024;  // wave-wide 1 KB copies per tensor tile
+  constexpr int LOADS_PER_TILE = 2 * INST_PER_TILE / NW;  // copy instructions per wave per tile
+  constexpr int RS = NSTAGE + 1;                    // row-map ring
   static_assert(INST_PER_TILE % NW == 0, "copies must split evenly over the waves");
 
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
-  unsigned char* Ks = smem;                      // [2][64 rows][256 B], chunk-swizzled
-  unsigned char* Vs = smem + 2 * TILE_BYTES;     // [2][64 rows][256 B], chunk-swizzled
-  int32_t* rowmap = reinterpret_cast<int32_t*>(smem + 4 * TILE_BYTES);  // [2][BN]
-  float* lw = reinterpret_cast<float*>(rowmap + 2 * BN);
-  int32_t* vstart = reinterpret_cast<int32_t*>(lw + ((p.Ck + 63) & ~63));
+  unsigned char* Ks = smem;                        // [NSTAGE][64 rows][256 B], chunk-swizzled
+  unsigned char* Vs = smem + NSTAGE * TILE_BYTES;  // [NSTAGE][64 rows][256 B], chunk-swizzled
+  int32_t* rowmap = reinterpret_cast<int32_t*>(smem + 2 * NSTAGE * TILE_BYTES);  // [RS][BN]
+  float* lw = reinterpret_cast<float*>(rowmap + RS * BN);  // [align64(Ck)] compensation biases
+  float* rag_bias = lw + ((p.Ck + 63) & ~63);              // [BN] bias of the ragged routed tile
+  int32_t* vstart = reinterpret_cast<int32_t*>(rag_bias + BN);
   int32_t* pstart = vstart + (p.Ck + 2);
 
   const int total = gridDim.x;
@@ -453,13 +489,15 @@ attn_bf16_d128_kernel(AttnArgs p) {
   const int nt_r = (n_r + BN - 1) / BN;
   const int nt_c = (a < Cq) ? (Ck + BN - 1) / BN : 0;
   const int T = nt_r + nt_c;
+  const int nt_full = n_r / BN;  // routed tiles with all 64 keys valid
+  if (tid < BN) rag_bias[tid] = (nt_full * BN + tid < n_r) ? 0.f : -INFINITY;
 
   const bf16_t* kh = static_cast<const bf16_t*>(p.kp) + (int64_t)bh * p.Nk * D;
   const bf16_t* vh = static_cast<const bf16_t*>(p.vp) + (int64_t)bh * p.Nk * D;
   const bf16_t* kc = p.kbar16 + (int64_t)bh * Ck * D;
   const bf16_t* vc = p.vbar16 + (int64_t)bh * Ck * D;
 
-  int cur = 0;
+  int cur = 0;  // segment cursor of threads 0..63 (virtual key position -> permuted row)
   auto map_tile = [&](int t) {
     if (tid < BN) {
       int phys;
@@ -469,42 +507,38 @@ attn_bf16_d128_kernel(AttnArgs p) {
           while (pos >= vstart[cur + 1]) ++cur;
           phys = pstart[cur] + (pos - vstart[cur]);
         } else {
-          phys = 0;
+          phys = 0;  // masked by rag_bias; any valid row
         }
       } else {
         const int b = (t - nt_r) * BN + tid;
         phys = b < Ck ? b : Ck - 1;
       }
-      rowmap[(t & 1) * BN + tid] = phys;
+      rowmap[(t % RS) * BN + tid] = phys;
     }
   };
 
   // one wave-wide copy moves rows 4*inst .. 4*inst+3 of a tile; lane -> (row, LDS chunk slot)
   const int cp_row = lane >> 4, cp_slot = lane & 15;
+  const uint32_t lds_k0 = lds_address(Ks), lds_v0 = lds_address(Vs);
   auto issue_loads = [&](int t) {
     const bf16_t* kb = t < nt_r ? kh : kc;
     const bf16_t* vb = t < nt_r ? vh : vc;
-    const int32_t* rm = rowmap + (t & 1) * BN;
-    unsigned char* kdst = Ks + (t & 1) * TILE_BYTES;
-    unsigned char* vdst = Vs + (t & 1) * TILE_BYTES;
+    const int32_t* rm = rowmap + (t % RS) * BN;
+    const uint32_t kdst = lds_k0 + (t % NSTAGE) * TILE_BYTES;
+    const uint32_t vdst = lds_v0 + (t % NSTAGE) * TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < INST_PER_TILE / NW; ++i) {
       const int inst = wave + i * NW;
       const int rr = 4 * inst + cp_row;
       const int64_t grow = (int64_t)rm[rr] * D;
-      const bf16_t* gk = kb + grow + ((cp_slot ^ (rr & 15)) << 3);
-      const bf16_t* gv = vb + grow + ((cp_slot ^ ((rr & 3) << 2)) << 3);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gk,
-                                       (__attribute__((address_space(3))) void*)(kdst + inst * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gv,
-                                       (__attribute__((address_space(3))) void*)(vdst + inst * 1024), 16, 0, 0);
+      async_copy_16B(kb + grow + ((cp_slot ^ (rr & 15)) << 3), __builtin_amdgcn_readfirstlane(kdst + inst * 1024));
+      async_copy_16B(vb + grow + ((cp_slot ^ ((rr & 3) << 2)) << 3), __builtin_amdgcn_readfirstlane(vdst + inst * 1024));
     }
   };
 
   // per-lane LDS byte offsets of the MFMA operands
-  int koff[KS];  // K row li (of a 32-row block), dims 16s + 8lh .. +7
-#pragma unroll
-  for (int s = 0; s < KS; ++s) koff[s] = li * 256 + (((2 * s + lh) ^ (li & 15)) << 4);
+  // K row li of a 32-row block, dims 16s + 8lh .. +7: chunk (2s + lh) ^ (li % 16)
+  const int koff0 = li * 256 + ((lh ^ (li & 15)) << 4);  // s = 0; other s: koff0 ^ (s << 5)
   int voff[DB];  // transpose read: group = lane/16 -> (dim half, key half); r = lane%16
   {
     const int r = lane & 15, g = lane >> 4, ddhalf = g & 1, khalf = g >> 1;
@@ -522,6 +556,9 @@ attn_bf16_d128_kernel(AttnArgs p) {
 #pragma unroll
     for (int s = 0; s < KS; ++s) bq[s] = as_bf16x8(*reinterpret_cast<const uint4*>(qr + 16 * s + 8 * lh));
   }
+  // Q must be in registers before the asynchronous tile copies start: the compiler does not
+  // see those copies and would otherwise wait for "its" loads inside the main loop
+  SVGEAR_WAIT_VMCNT(0);
 
   f32x16 oacc[DB];
 #pragma unroll
@@ -531,102 +568,164 @@ attn_bf16_d128_kernel(AttnArgs p) {
   float m = -INFINITY, l = 0.f;
   const float c = p.scale * kLog2e;
 
-  if (T > 0) {
-    map_tile(0);
-    if (T > 1) map_tile(1);
-    __syncthreads();
-    issue_loads(0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-  }
+  auto rescale = [&](float m_new) {
+    const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
+    l *= alpha;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    m = m_new;
+  };
 
-  for (int t = 0; t < T; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < T) issue_loads(t + 1);
-    if (wave_active) {
-      const unsigned char* Kb = Ks + buf * TILE_BYTES;
-      const unsigned char* Vb = Vs + buf * TILE_BYTES;
-      f32x16 sacc[2];
+  // One 64-key tile for this wave's 32 queries. BIASED = false: a full routed tile.
+  // BIASED = true: per-key additive bias (ragged routed tile: 0 / -inf; compensation tile:
+  // log2|k_b| or -inf).
+  auto compute_tile = [&](int t, auto biased_tag) {
+    constexpr bool BIASED = decltype(biased_tag)::value;
+    const unsigned char* Kb = Ks + (t % NSTAGE) * TILE_BYTES;
+    const unsigned char* Vb = Vs + (t % NSTAGE) * TILE_BYTES;
+    // ---- S^T = K Q^T : 64 keys x 32 queries; register r of block kb is key
+    // 32kb + 8(r/4) + 4lh + r%4, query li
+    f32x16 sacc[2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+    {
+      // operand reads run one 32-key block ahead of the MFMAs that consume them
+      bf16x8 ak0[KS], ak1[KS];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          const bf16x8 ak = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + kb * 32 * 256 + koff[s]));
-          sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[s], sacc[kb], 0, 0, 0);
-        }
+      for (int s = 0; s < KS; ++s) ak0[s] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (koff0 ^ (s << 5))));
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        ak1[s] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + 32 * 256 + (koff0 ^ (s << 5))));
+#pragma unroll
+      for (int s = 0; s < KS; ++s) sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak0[s], bq[s], sacc[0], 0, 0, 0);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak1[s], bq[s], sacc[1], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);  // DS reads of block 0
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA of block 0
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one DS read of block 1
       }
-      float mx = -INFINITY;
-      if (t < nt_r) {
-        const int left = n_r - t * BN;
-        if (left < BN) {
+      __builtin_amdgcn_sched_group_barrier(0x008, KS, 0);  // MFMAs of block 1
+    }
+    // ---- online softmax in the base-2 domain; the running maximum m is refreshed lazily
+    // (only when a score exceeds it by more than 2^kLazyRescale), so O is rarely rescaled
+    uint32_t pk[2][8];
+    if constexpr (!BIASED) {
+      float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (32 * kb + 8 * (r >> 2) + 4 * lh + (r & 3) >= left) sacc[kb][r] = -INFINITY;
-        }
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            sacc[kb][r] *= c;
-            mx = fmaxf(mx, sacc[kb][r]);
-          }
-      } else {
-        const float* lwt = lw + (t - nt_r) * BN;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const float4 bias = *reinterpret_cast<const float4*>(lwt + 32 * kb + 8 * g + 4 * lh);
-            sacc[kb][4 * g + 0] = __builtin_fmaf(sacc[kb][4 * g + 0], c, bias.x);
-            sacc[kb][4 * g + 1] = __builtin_fmaf(sacc[kb][4 * g + 1], c, bias.y);
-            sacc[kb][4 * g + 2] = __builtin_fmaf(sacc[kb][4 * g + 2], c, bias.z);
-            sacc[kb][4 * g + 3] = __builtin_fmaf(sacc[kb][4 * g + 3], c, bias.w);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[kb][4 * g + r]);
-          }
-      }
+      for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m, mx);
-      if (__any(m_new > m)) {
-        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
-        l *= alpha;
+      const float ms = mx * c;
+      if (__any(ms > m + kLazyRescale)) rescale(fmaxf(m, ms));
+      const float neg_m = -m;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-        m = m_new;
-      }
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, neg_m));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r + 1], c, neg_m));
+          pk[kb][r >> 1] = pack_bf16(p0, p1);
+        }
+    } else {
+      const float* lwt = t < nt_r ? rag_bias : lw + (t - nt_r) * BN;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 bias = *reinterpret_cast<const float4*>(lwt + 32 * kb + 8 * g + 4 * lh);
+          sacc[kb][4 * g + 0] = __builtin_fmaf(sacc[kb][4 * g + 0], c, bias.x);
+          sacc[kb][4 * g + 1] = __builtin_fmaf(sacc[kb][4 * g + 1], c, bias.y);
+          sacc[kb][4 * g + 2] = __builtin_fmaf(sacc[kb][4 * g + 2], c, bias.z);
+          sacc[kb][4 * g + 3] = __builtin_fmaf(sacc[kb][4 * g + 3], c, bias.w);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[kb][4 * g + r]);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      if (__any(mx > m + kLazyRescale)) rescale(fmaxf(m, mx));
       const float m_use = (m == -INFINITY) ? 0.f : m;
-      uint32_t pk[2][8];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
           const float p0 = __builtin_amdgcn_exp2f(sacc[kb][r] - m_use);
           const float p1 = __builtin_amdgcn_exp2f(sacc[kb][r + 1] - m_use);
-          l += p0 + p1;
           pk[kb][r >> 1] = pack_bf16(p0, p1);
         }
+    }
+    // row sums from the bf16-rounded probabilities (the values the PV product uses)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) l = dot2_ones(pk[kb][u], l);
+    // ---- O^T += V^T P^T : k-step ks covers keys 16ks .. 16ks+15; the transpose reads of
+    // k-step ks+1 are issued before the MFMAs of k-step ks
+    {
+      bf16x8 av[4][DB];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) av[ks][db] = tr_pair(Vb, ks * 16 * 256 + voff[db]);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int kb = ks >> 1, u4 = (ks & 1) * 4;
         const bf16x8 bp = as_bf16x8(make_uint4(pk[kb][u4], pk[kb][u4 + 1], pk[kb][u4 + 2], pk[kb][u4 + 3]));
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 av = tr_pair(Vb, ks * 16 * 256 + voff[db]);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bp, oacc[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks][db], bp, oacc[db], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 1);  // reads of k-step 0
+#pragma unroll
+      for (int ks = 0; ks < 3; ++ks)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);  // MFMA (ks, db)
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);  // the two reads of operand (ks+1, db)
+        }
+      __builtin_amdgcn_sched_group_barrier(0x008, DB, 1);
     }
-    if (t + 2 < T) map_tile(t + 2);
-    __builtin_amdgcn_s_waitcnt(0);  // this wave's copies of tile t+1 have landed in LDS
+  };
+
+  // pipeline step around the compute of tile t
+  auto step_begin = [&](int t) {
+    if (t + NSTAGE - 1 < T) issue_loads(t + NSTAGE - 1);
+  };
+  auto step_end = [&](int t) {
+    if (t + NSTAGE < T) map_tile(t + NSTAGE);
+    // this wave's copies of tile t+1 must have landed; younger tiles may stay in flight
+    if (t + NSTAGE - 1 < T) SVGEAR_WAIT_VMCNT((NSTAGE - 2) * LOADS_PER_TILE);
+    else SVGEAR_WAIT_VMCNT(0);
     __syncthreads();
+  };
+
+  // prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed
+#pragma unroll
+  for (int t = 0; t < NSTAGE; ++t)
+    if (t < T) map_tile(t);
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t)
+    if (t < T) issue_loads(t);
+  if (T >= NSTAGE - 1) SVGEAR_WAIT_VMCNT((NSTAGE - 2) * LOADS_PER_TILE);
+  else SVGEAR_WAIT_VMCNT(0);
+  __syncthreads();
+
+  for (int t = 0; t < nt_full; ++t) {
+    step_begin(t);
+    if (wave_active) compute_tile(t, std::false_type{});
+    step_end(t);
+  }
+  for (int t = nt_full; t < T; ++t) {
+    step_begin(t);
+    if (wave_active) compute_tile(t, std::true_type{});
+    step_end(t);
   }
 
+  // ---- epilogue: lane holds query li, dims 32db + 8g + 4lh + 0..3
   if (wave_active) {
     const float lt = l + __shfl_xor(l, 32);
     if (qvalid) {
@@ -648,7 +747,16 @@ attn_bf16_d128_kernel(AttnArgs p) {
 
 }  // namespace
 
-size_t attn_bf16_lds_bytes(int d, int Ck) { return d == 128 ? lds_bytes_d128(Ck) : lds_bytes_generic(d, Ck); }
+// Tile shape of the d = 128 kernel: 8 waves x 32 query rows per workgroup (one workgroup per
+// CU, 2 waves per SIMD), 4 K/V tile buffers in flight.
+constexpr int kD128Waves = 8;
+constexpr int kD128Stages = 4;
+
+int attn_bf16_bm(int d) { return d == 128 ? 32 * kD128Waves : 32 * kBf16Waves; }
+
+size_t attn_bf16_lds_bytes(int d, int Ck) {
+  return d == 128 ? lds_bytes_d128(Ck, kD128Stages) : lds_bytes_generic(d, Ck);
+}
 
 int launch_attn_bf16(const AttnArgs& a, int d, unsigned total, hipStream_t s) {
   const size_t lds = attn_bf16_lds_bytes(d, a.Ck);
@@ -658,10 +766,10 @@ int launch_attn_bf16(const AttnArgs& a, int d, unsigned total, hipStream_t s) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     kern<<<total, 64 * kBf16Waves, lds, s>>>(a);
   } else {
-    auto kern = attn_bf16_d128_kernel<kBf16Waves>;
+    auto kern = attn_bf16_d128_kernel<kD128Waves, kD128Stages>;
     SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<total, 64 * kBf16Waves, lds, s>>>(a);
+    kern<<<total, 64 * kD128Waves, lds, s>>>(a);
   }
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;
