@@ -9,6 +9,12 @@
 // k-steps accumulates every (centroid, row) pair in exactly that order (one fused
 // multiply-add with one rounding per element of the contraction, k ascending), which was
 // checked bit for bit against a scalar fmaf chain on gfx950.
+// For bf16 inputs a cheap FILTER runs first: the same scores from bf16 MFMAs (the centroid
+// split exactly into two bf16 pieces plus a residual below 2^-16), with the best and the
+// second-best score tracked per row. A row whose margin exceeds a rigorous bound on
+// |filter score - fixed-order score| keeps the filter's label (the fixed-order argmin is
+// provably the same); the few remaining rows are re-assigned by the fp32 kernel, so the
+// labels are always those of the fixed-order definition.
 // Update: members are brought into cluster order by the stable counting sort, then summed
 // in a fixed order (interleaved partial sums per cluster, combined in slot order) -- no float
 // atomics, so the centroids are run-to-run deterministic.
@@ -31,12 +37,32 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 //    blk (32 centroids), group q (4 consecutive k-steps), lane, j hold
 //    cent[32 blk + lane%32][2 (4q + j) + lane/32], so a lane fetches the operands of four
 //    MFMAs with one 16-byte read and a wave reads 1 KB contiguously.
+//  * chl (optional): the bf16 split c = hi + lo + residual, hi = bf16(c), lo = bf16(c - hi), in
+//    the operand order of v_mfma_f32_32x32x16_bf16 (A[i = lane%32][k = 16s + 8(lane/32) + e]):
+//    [blk][piece][s][lane][e], 16 bytes per lane;
+//  * amb_count (optional) is reset for the filter pass.
 __global__ void __launch_bounds__(256)
 prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, float* __restrict__ cperm,
-                      float* __restrict__ cn) {
+                      float* __restrict__ cn, bf16_t* __restrict__ chl, int32_t* __restrict__ amb_count) {
   const int bh = blockIdx.y;
   const float* cb = cent + (int64_t)bh * C * d;
   const int64_t n = (int64_t)Cpad * d;
+  if (amb_count && blockIdx.x == 0 && threadIdx.x == 0) amb_count[bh] = 0;
+  if (chl) {
+    const int ksn = d / 16;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+      const int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+      const int64_t rest = i >> 9;  // blk * ksn + s
+      const int sidx = (int)(rest % ksn), blk = (int)(rest / ksn);
+      const int c = 32 * blk + (lane & 31), k = 16 * sidx + 8 * (lane >> 5) + e;
+      const float v = c < C ? cb[(int64_t)c * d + k] : 0.f;
+      const bf16_t hi = f32_to_bf16(v);
+      const bf16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
+      const int64_t base = (int64_t)bh * 2 * n + (((int64_t)blk * 2) * ksn + sidx) * 512 + lane * 8 + e;
+      chl[base] = hi;
+      chl[base + (int64_t)ksn * 512] = lo;
+    }
+  }
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const int j = (int)(i & 3), lane = (int)((i >> 2) & 63);
     const int64_t rest = i >> 8;  // blk * (d/8) + q
@@ -92,10 +118,12 @@ __device__ __forceinline__ void load_row_operands(const bf16_t* xr, int h, float
 // (min, argmin) in ascending centroid order; the two lanes of a row merge once at the end.
 // Centroid chunks (64 centroids, in operand order) stream through two LDS stages with
 // asynchronous global-to-LDS copies shared by the 8 waves (256 rows) of the workgroup.
+// With row_list != nullptr only the rows listed there (row_count[bh] of them) are assigned.
 template <typename T, int D>
 __global__ void __launch_bounds__(64 * kAssignWaves)
 assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const float* __restrict__ cperm,
-                   const float* __restrict__ cn, int Cpad, int32_t* __restrict__ labels) {
+                   const float* __restrict__ cn, int Cpad, int32_t* __restrict__ labels,
+                   const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count) {
   constexpr int QG = D / 8;                        // 16-byte operand groups per block
   constexpr int CHUNK_BYTES = kCentChunk * D * 4;  // one LDS stage of centroids
   constexpr int COPIES = CHUNK_BYTES / 1024 / kAssignWaves;
@@ -105,10 +133,13 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const int bh = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t row = (int64_t)blockIdx.x * kAssignRows + 32 * wave + li;
-  const int64_t lrow = row < nv ? row : nv - 1;
+  const int64_t n_rows = row_list ? row_count[bh] : nv;
+  if ((int64_t)blockIdx.x * kAssignRows >= n_rows) return;
+  const int64_t pos = (int64_t)blockIdx.x * kAssignRows + 32 * wave + li;
+  const int64_t lpos = pos < n_rows ? pos : n_rows - 1;
+  const int64_t row = row_list ? row_list[(int64_t)bh * nv + lpos] : lpos;
   float xb[D / 2];
-  load_row_operands<D>(x + head_base(st, bh, H) + lrow * st.n, lh, xb);
+  load_row_operands<D>(x + head_base(st, bh, H) + row * st.n, lh, xb);
   SVGEAR_WAIT_VMCNT(0);  // rows are in registers before the asynchronous copies start
 
   const unsigned char* cp = reinterpret_cast<const unsigned char*>(cperm + (int64_t)bh * Cpad * D);
@@ -185,7 +216,171 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const float ob = __shfl_xor(best, 32);
   const int oa = __shfl_xor(arg, 32);
   if (ob < best || (ob == best && oa < arg)) arg = oa;
-  if (lh == 0 && row < nv) labels[(int64_t)bh * nv + row] = arg;
+  if (lh == 0 && pos < n_rows) labels[(int64_t)bh * nv + row] = arg;
+}
+
+// ---- bf16 filter -----------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
+  union { uint4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
+
+constexpr int kFilterWaves = 8;
+constexpr int kFilterRowsPerWave = 64;  // two 32-row operand sets share every centroid fragment
+constexpr int kFilterRows = kFilterWaves * kFilterRowsPerWave;
+
+// |x|_2 of every row (fp32), once per call: the input does not change between iterations.
+template <int D>
+__global__ void __launch_bounds__(256)
+row_norm_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, float* __restrict__ xnorm) {
+  const int bh = blockIdx.y;
+  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (row >= nv) return;
+  const bf16_t* xr = x + head_base(st, bh, H) + row * st.n;
+  float acc = 0.f;
+#pragma unroll
+  for (int t = 0; t < D; t += 4) {
+    const float4 v = load4(xr + t);
+    acc = __builtin_fmaf(v.x, v.x, acc);
+    acc = __builtin_fmaf(v.y, v.y, acc);
+    acc = __builtin_fmaf(v.z, v.z, acc);
+    acc = __builtin_fmaf(v.w, v.w, acc);
+  }
+  xnorm[(int64_t)bh * nv + row] = sqrtf(acc) * 1.00002f;  // upper bound (the fp32 sum is within d 2^-24)
+}
+
+// Approximate scores s~(c) = fma(-2, x.hi_c + x.lo_c, |c|^2) on bf16 MFMAs, with the best and
+// second-best kept per row. With X = |x|_2, Cm = max_c |c|_2 and d the head dimension,
+//   |x.c(filter) - x.c(fixed order)| <= X Cm (2^-16 + (2d+1) 2^-23 + d 2^-24) =: X Cm kappa
+// (split residual below 2^-16 |c| per element; every fp32 addition inside the matrix core
+// charged 2^-23 relative, twice the round-to-nearest unit, over 2d+1 terms in any order; the
+// fixed-order chain charged the usual d 2^-24), the two final fmas add 2^-23 (Cm^2 + 2 X Cm),
+// so two scores differ from their fixed-order values by at most
+//   B = 2 X Cm kappa + 2^-23 (Cm^2 + 2 X Cm).
+// If second - best > 2B the fixed-order argmin is the filter's argmin; otherwise the row is
+// queued for the exact kernel.
+template <int D>
+__global__ void __launch_bounds__(64 * kFilterWaves)
+assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, const bf16_t* __restrict__ chl,
+                     const float* __restrict__ cn, const float* __restrict__ xnorm, int C, int Cpad,
+                     int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count) {
+  constexpr int KSN = D / 16;
+  constexpr int CHUNK_BYTES = kCentChunk * D * 2 * 2;  // 64 centroids, hi and lo pieces
+  constexpr int COPIES = CHUNK_BYTES / 1024 / kFilterWaves;
+  static_assert(CHUNK_BYTES % (1024 * kFilterWaves) == 0, "chunk copies must split over the waves");
+  extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
+  float* cns = reinterpret_cast<float*>(smem + 2 * CHUNK_BYTES);  // [2][kCentChunk]
+  float* red = cns + 2 * kCentChunk;                              // [64 * kFilterWaves]
+  const int bh = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const float* cnb = cn + (int64_t)bh * Cpad;
+
+  // Cm^2 = max |c|^2 over the real centroids
+  float cm2 = 0.f;
+  for (int c = tid; c < C; c += 64 * kFilterWaves) cm2 = fmaxf(cm2, cnb[c]);
+  red[tid] = cm2;
+  __syncthreads();
+  for (int w = 32 * kFilterWaves; w > 0; w >>= 1) {
+    if (tid < w) red[tid] = fmaxf(red[tid], red[tid + w]);
+    __syncthreads();
+  }
+  const float Cm = sqrtf(red[0]) * 1.00002f;  // upper bound
+
+  // B operands: rows of two 32-row sets, dims 16s + 8 lh .. +7
+  int64_t rows[2];
+  bf16x8 bx[2][KSN];
+#pragma unroll
+  for (int rs = 0; rs < 2; ++rs) {
+    rows[rs] = (int64_t)blockIdx.x * kFilterRows + kFilterRowsPerWave * wave + 32 * rs + li;
+    const int64_t lrow = rows[rs] < nv ? rows[rs] : nv - 1;
+    const bf16_t* xr = x + head_base(st, bh, H) + lrow * st.n;
+#pragma unroll
+    for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(*reinterpret_cast<const uint4*>(xr + 16 * s + 8 * lh));
+  }
+  SVGEAR_WAIT_VMCNT(0);
+
+  const unsigned char* cp = reinterpret_cast<const unsigned char*>(chl + (int64_t)bh * 2 * Cpad * D);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const int nchunks = Cpad / kCentChunk;
+  auto issue_chunk = [&](int ch) {
+    const unsigned char* src = cp + (int64_t)ch * CHUNK_BYTES;
+    const uint32_t dst = lds0 + (ch & 1) * CHUNK_BYTES;
+#pragma unroll
+    for (int i = 0; i < COPIES; ++i) {
+      const int inst = wave + i * kFilterWaves;
+      async_copy_16B(src + inst * 1024 + lane * 16, __builtin_amdgcn_readfirstlane(dst + inst * 1024));
+    }
+  };
+
+  float best[2] = {INFINITY, INFINITY}, second[2] = {INFINITY, INFINITY};
+  int arg[2] = {0, 0};
+  issue_chunk(0);
+  if (tid < kCentChunk) cns[tid] = cnb[tid];
+  SVGEAR_WAIT_VMCNT(0);
+  __syncthreads();
+  for (int ch = 0; ch < nchunks; ++ch) {
+    float cn_next = 0.f;
+    if (ch + 1 < nchunks) {
+      issue_chunk(ch + 1);
+      if (tid < kCentChunk) cn_next = cnb[(ch + 1) * kCentChunk + tid];
+    }
+    const float* cnc = cns + (ch & 1) * kCentChunk;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      // block layout in the stage: [piece][s][lane][8 bf16]
+      const unsigned char* cb = smem + (ch & 1) * CHUNK_BYTES + blk * (2 * KSN * 1024) + lane * 16;
+      f32x16 acc0, acc1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.f;
+#pragma unroll
+      for (int ps = 0; ps < 2 * KSN; ++ps) {
+        const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(cb + ps * 1024));
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[0][ps % KSN], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[1][ps % KSN], acc1, 0, 0, 0);
+      }
+      // register r is centroid 8(r/4) + 4 lh + r%4 of the block, row li of the set
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 n4 = *reinterpret_cast<const float4*>(cnc + 32 * blk + 8 * g + 4 * lh);
+        const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int idx = ch * kCentChunk + 32 * blk + 8 * g + 4 * lh + r;
+          const float s0 = __builtin_fmaf(-2.0f, acc0[4 * g + r], nn[r]);
+          const float s1 = __builtin_fmaf(-2.0f, acc1[4 * g + r], nn[r]);
+          second[0] = __builtin_amdgcn_fmed3f(s0, best[0], second[0]);
+          second[1] = __builtin_amdgcn_fmed3f(s1, best[1], second[1]);
+          if (s0 < best[0]) { best[0] = s0; arg[0] = idx; }
+          if (s1 < best[1]) { best[1] = s1; arg[1] = idx; }
+        }
+      }
+    }
+    if (ch + 1 < nchunks && tid < kCentChunk) cns[((ch + 1) & 1) * kCentChunk + tid] = cn_next;
+    SVGEAR_WAIT_VMCNT(0);
+    __syncthreads();
+  }
+  constexpr float kappa = 1.52587890625e-05f + (2 * D + 1) * 1.1920928955078125e-07f + D * 5.9604644775390625e-08f;
+#pragma unroll
+  for (int rs = 0; rs < 2; ++rs) {
+    // merge the two lanes of a row (each saw half of the centroids)
+    const float ob = __shfl_xor(best[rs], 32), os = __shfl_xor(second[rs], 32);
+    const int oa = __shfl_xor(arg[rs], 32);
+    const float lo = fminf(best[rs], ob), hi = fmaxf(best[rs], ob);
+    const float sec = fminf(hi, fminf(second[rs], os));
+    const int a = (ob < best[rs] || (ob == best[rs] && oa < arg[rs])) ? oa : arg[rs];
+    if (lh == 0 && rows[rs] < nv) {
+      const float X = xnorm[(int64_t)bh * nv + rows[rs]];
+      const float B = 2.0f * X * Cm * kappa + 1.1920928955078125e-07f * (Cm * Cm + 2.0f * X * Cm);
+      labels[(int64_t)bh * nv + rows[rs]] = a;
+      if (!(sec - lo > 2.0f * B * 1.0001f)) {  // also catches NaN / inf margins
+        const int slot = atomicAdd(&amb_count[bh], 1);
+        amb_rows[(int64_t)bh * nv + slot] = (int32_t)rows[rs];
+      }
+    }
+  }
 }
 
 // Mean of the members of one cluster. A row is covered by LPR lanes of 16 bytes each; the
@@ -255,17 +450,37 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   int32_t* offsets = ws.take<int32_t>((size_t)BH * (C + 2));
   float* cn = ws.take<float>((size_t)BH * Cpad);
   float* cperm = ws.take<float>((size_t)BH * Cpad * D);
+  constexpr bool kFilter = sizeof(T) == 2;  // bf16 input: filter on bf16 MFMAs, then exact on the ambiguous rows
+  bf16_t* chl = kFilter ? ws.take<bf16_t>((size_t)BH * 2 * Cpad * D) : nullptr;
+  float* xnorm = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
+  int32_t* amb_rows = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
+  int32_t* amb_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
   if (!ws.ok()) return SVGEAR_ERR_WORKSPACE;
   const size_t lds = 2 * (size_t)kCentChunk * D * 4 + 2 * kCentChunk * sizeof(float);
   auto assign = assign_mfma_kernel<T, D>;
   SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  const size_t lds_f = 2 * (size_t)kCentChunk * D * 4 + (2 * kCentChunk + 64 * kFilterWaves) * sizeof(float);
+  if constexpr (kFilter) {
+    SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
+    row_norm_kernel<D><<<dim3((unsigned)ceil_div(nv, 256), BH), 256, 0, s>>>(
+        reinterpret_cast<const bf16_t*>(x), st, H, nv, xnorm);
+    SVGEAR_LAUNCH_CHECK();
+  }
   const dim3 gp((unsigned)ceil_div((int64_t)Cpad * D, 256 * 4), BH);
   const dim3 ga((unsigned)ceil_div(nv, kAssignRows), BH);
   for (int it = 0; it < iters; ++it) {
-    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn);
+    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count);
     SVGEAR_LAUNCH_CHECK();
-    assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels);
+    if constexpr (kFilter) {
+      assign_filter_kernel<D><<<dim3((unsigned)ceil_div(nv, kFilterRows), BH), 64 * kFilterWaves, lds_f, s>>>(
+          reinterpret_cast<const bf16_t*>(x), st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count);
+      SVGEAR_LAUNCH_CHECK();
+      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, amb_rows, amb_count);
+    } else {
+      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, nullptr, nullptr);
+    }
     SVGEAR_LAUNCH_CHECK();
     int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s);
     if (rc != SVGEAR_OK) return rc;
@@ -289,7 +504,9 @@ extern "C" size_t svgear_kmeans_workspace(int B, int H, int64_t N, int d, int C)
   const size_t BH = (size_t)B * H;
   const size_t Cpad = align_up(C, kCentChunk);
   return align_up(BH * sort_chunks(N) * (C + 1) * 4, 256) + align_up(BH * N * 4, 256) +
-         align_up(BH * (C + 2) * 4, 256) + align_up(BH * Cpad * 4, 256) + align_up(BH * Cpad * d * 4, 256);
+         align_up(BH * (C + 2) * 4, 256) + align_up(BH * Cpad * 4, 256) + align_up(BH * Cpad * d * 4, 256) +
+         // bf16 filter: hi/lo operand tables, row norms, ambiguous-row list and counter
+         align_up(BH * 2 * Cpad * d * 2, 256) + 2 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256);
 }
 
 extern "C" int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, int64_t N,
