@@ -593,24 +593,22 @@ attn_bf16_d128_kernel(AttnArgs p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
     {
-      // operand reads run one 32-key block ahead of the MFMAs that consume them
-      bf16x8 ak0[KS], ak1[KS];
+      // the two 32-key blocks alternate so that consecutive MFMAs are independent; operand
+      // reads run four fragments ahead of the MFMAs that consume them
+      bf16x8 ak[2 * KS];
 #pragma unroll
-      for (int s = 0; s < KS; ++s) ak0[s] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (koff0 ^ (s << 5))));
+      for (int i = 0; i < 2 * KS; ++i)
+        ak[i] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (i & 1) * 32 * 256 + (koff0 ^ ((i >> 1) << 5))));
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
-        ak1[s] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + 32 * 256 + (koff0 ^ (s << 5))));
+      for (int i = 0; i < 2 * KS; ++i)
+        sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[i], bq[i >> 1], sacc[i & 1], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-      for (int s = 0; s < KS; ++s) sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak0[s], bq[s], sacc[0], 0, 0, 0);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak1[s], bq[s], sacc[1], 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);  // DS reads of block 0
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA of block 0
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one DS read of block 1
+      for (int i = 0; i < 2 * KS - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, KS, 0);  // MFMAs of block 1
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
     // ---- online softmax in the base-2 domain; the running maximum m is refreshed lazily
     // (only when a score exceeds it by more than 2^kLazyRescale), so O is rarely rescaled
