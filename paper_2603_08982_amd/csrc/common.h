@@ -94,4 +94,9 @@ static inline int64_t sort_chunks(int64_t N) { return ceil_div(N, kSortChunk); }
 int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C, int32_t* perm,
                 int32_t* offsets, int32_t* chunk_hist, hipStream_t s);
 
+
+// Per-head length of the probe's per-key statistic arrays (padded so that 16-byte reads
+// starting at any key stay inside the array).
+static inline int64_t probe_stat_stride(int64_t Nk) { return (int64_t)align_up((size_t)Nk + 64, 64); }
+
 }  // namespace svgear

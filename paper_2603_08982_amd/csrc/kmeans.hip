@@ -74,8 +74,19 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
     float acc = INFINITY;
     if (c < C) {
       acc = 0.f;
-      const float* cr = cb + (int64_t)c * d;
-      for (int t = 0; t < d; ++t) acc = __builtin_fmaf(cr[t], cr[t], acc);
+      const float4* cr = reinterpret_cast<const float4*>(cb + (int64_t)c * d);
+      for (int t0 = 0; t0 < d / 4; t0 += 8) {  // 8 independent 16-byte loads, then the chain in order
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = cr[t0 + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          acc = __builtin_fmaf(v[u].x, v[u].x, acc);
+          acc = __builtin_fmaf(v[u].y, v[u].y, acc);
+          acc = __builtin_fmaf(v[u].z, v[u].z, acc);
+          acc = __builtin_fmaf(v[u].w, v[u].w, acc);
+        }
+      }
     }
     cn[(int64_t)bh * Cpad + c] = acc;
   }

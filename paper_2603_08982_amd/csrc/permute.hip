@@ -69,39 +69,44 @@ scan_kernel(int32_t* __restrict__ chunk_hist, int64_t N, int C, int nchunks,
   if (threadIdx.x == 0) o[C + 1] = (int32_t)N;
 }
 
+// Stable placement: tokens of a chunk are taken 256 at a time; inside a wave the rank of a
+// token among the lanes with the same label comes from ballots over the label bits, and the
+// four waves of the workgroup claim their positions one after the other (wave order = token
+// order), so equal labels keep ascending token order without any atomic.
 __global__ void __launch_bounds__(kThreads)
 scatter_kernel(const int32_t* __restrict__ labels, int64_t N, int64_t nv, int C, int nchunks,
                const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ perm) {
-  extern __shared__ int32_t sm[];  // base[C+1], lab_s[kThreads]
-  int32_t* base = sm;
-  int32_t* lab_s = sm + (C + 1);
+  extern __shared__ int32_t base[];  // C+1 next free position per label
   const int bh = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* hist = chunk_hist + ((int64_t)bh * nchunks + chunk) * (C + 1);
   for (int c = threadIdx.x; c <= C; c += kThreads) base[c] = hist[c];
   const int32_t* lab = labels + (int64_t)bh * nv;
   int32_t* out = perm + (int64_t)bh * N;
   const int64_t lo = (int64_t)chunk * kSortChunk;
+  const int nbits = 32 - __clz(C + 1);
+  const uint64_t below = (1ull << lane) - 1ull;
+  __syncthreads();
   for (int sub = 0; sub < kSortChunk / kThreads; ++sub) {
+    if (lo + (int64_t)sub * kThreads >= N) break;
     const int64_t i = lo + (int64_t)sub * kThreads + threadIdx.x;
     const bool valid = i < N;
-    const int my = valid ? token_label(lab, i, nv, C) : -1;
-    __syncthreads();  // previous round's base updates and lab_s reads are done
-    lab_s[threadIdx.x] = my;
-    __syncthreads();
-    int rank = 0, total = 0;
-    for (int k = 0; k < kThreads; ++k) {
-      const int same = (lab_s[k] == my);
-      total += same;
-      rank += same & (k < (int)threadIdx.x);
+    const int my = valid ? token_label(lab, i, nv, C) : (C + 1);
+    uint64_t same = ~0ull;
+    for (int bit = 0; bit < nbits; ++bit) {
+      const uint64_t vote = __ballot((my >> bit) & 1);
+      same &= ((my >> bit) & 1) ? vote : ~vote;
     }
-    int b = 0;
-    if (valid) {
-      b = base[my];
-      out[b + rank] = (int32_t)i;
+    const int rank = __popcll(same & below);
+    const int total = __popcll(same);
+    for (int w = 0; w < kThreads / 64; ++w) {
+      if (wave == w && valid) {
+        const int b = base[my];
+        out[b + rank] = (int32_t)i;
+        if (rank == total - 1) base[my] = b + total;  // issued after every lane's read of base
+      }
+      __syncthreads();
     }
-    __syncthreads();
-    if (valid && rank == total - 1) base[my] = b + total;
-    if (lo + (int64_t)(sub + 1) * kThreads >= N) break;
   }
 }
 
@@ -149,7 +154,7 @@ int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C,
   SVGEAR_LAUNCH_CHECK();
   scan_kernel<<<BH, kThreads, 2 * (C + 1) * sizeof(int32_t), s>>>(chunk_hist, N, C, nchunks, offsets);
   SVGEAR_LAUNCH_CHECK();
-  scatter_kernel<<<grid, kThreads, (C + 1 + kThreads) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks,
+  scatter_kernel<<<grid, kThreads, (C + 1) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks,
                                                                             chunk_hist, perm);
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;

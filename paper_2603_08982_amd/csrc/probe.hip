@@ -20,16 +20,36 @@ constexpr int kKeyChunk = 64;
 constexpr float kMaxExponent = 40.0f;  // e^40 squared still fits fp32
 
 // Sbar[a][b] = qbar_a . kbar_b * scale; mrow[a] = max over non-empty b.
+// With q3 != nullptr (grid.x = Cq rounded up to 32) it also writes qbar split into three bf16
+// pieces q = hi + mid + lo (exact: 3 x 8 significant bits), laid out as B operands of
+// v_mfma_f32_32x32x16_bf16: [a-block][piece][s][lane = a%32 + 32*((k%16)/8)][k%8], zero rows
+// for a >= Cq.
 template <int D>
 __global__ void __launch_bounds__(256)
 sbar_kernel(const float* __restrict__ qbar, const float* __restrict__ kbar, const int32_t* __restrict__ k_offsets,
-            int Cq, int Ck, float scale, float* __restrict__ sbar, float* __restrict__ mrow) {
+            int Cq, int Ck, float scale, float* __restrict__ sbar, float* __restrict__ mrow,
+            bf16_t* __restrict__ q3) {
   __shared__ float q[D];
   __shared__ float red[256];
   const int a = blockIdx.x, bh = blockIdx.y;
-  const float* qa = qbar + ((int64_t)bh * Cq + a) * D;
-  for (int t = threadIdx.x; t < D; t += 256) q[t] = qa[t];
+  const float* qa = qbar + ((int64_t)bh * Cq + (a < Cq ? a : 0)) * D;
+  for (int t = threadIdx.x; t < D; t += 256) q[t] = a < Cq ? qa[t] : 0.f;
   __syncthreads();
+  if (q3 && threadIdx.x < D) {
+    constexpr int KSN = D / 16;
+    const int k = threadIdx.x, ab = a >> 5, nab = (Cq + 31) >> 5;
+    const float v = q[k];
+    const bf16_t hi = f32_to_bf16(v);
+    const float r1 = v - bf16_to_f32(hi);
+    const bf16_t mid = f32_to_bf16(r1);
+    const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+    const int lane = (a & 31) + 32 * ((k & 15) >> 3);
+    bf16_t* dst = q3 + ((((int64_t)bh * nab + ab) * 3) * KSN + (k >> 4)) * 512 + lane * 8 + (k & 7);
+    dst[0] = hi;
+    dst[(int64_t)KSN * 512] = mid;
+    dst[(int64_t)2 * KSN * 512] = lo;
+  }
+  if (a >= Cq) return;
   const int32_t* off = k_offsets + (int64_t)bh * (Ck + 2);
   float mx = -INFINITY;
   for (int b = threadIdx.x; b < Ck; b += 256) {
@@ -156,29 +176,188 @@ block_error_kernel(const float* __restrict__ qbar, const float* __restrict__ vba
   if (live) *out = E / (float)(end - start);
 }
 
+// ---- bf16 inputs: the probe on the matrix cores -----------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
+  union { uint4 u; bf16x8 b; } c;
+  c.u = v;
+  return c.b;
+}
+
+// |delta_j|^2 and vbar . delta_j of every clustered key (delta_j = v_j - vbar of its cluster).
+// One workgroup per (head, key cluster): 16 key slots x 16 lanes of 8 dims.
+template <int D>
+__global__ void __launch_bounds__(256)
+value_stats_kernel(const float* __restrict__ vbar, const bf16_t* __restrict__ vp,
+                   const int32_t* __restrict__ k_offsets, int64_t Nk, int64_t stat_stride, int Ck,
+                   float* __restrict__ nd, float* __restrict__ dd) {
+  constexpr int LPK = D / 8;  // lanes per key
+  constexpr int SLOTS = 256 / LPK;
+  const int b = blockIdx.x, bh = blockIdx.y;
+  const int slot = threadIdx.x / LPK, lane = threadIdx.x % LPK;
+  const int32_t* off = k_offsets + (int64_t)bh * (Ck + 2);
+  const int start = off[b], end = off[b + 1];
+  const float* vb = vbar + ((int64_t)bh * Ck + b) * D + lane * 8;
+  float vbl[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) vbl[k] = vb[k];
+  const bf16_t* vh = vp + (int64_t)bh * Nk * D + lane * 8;
+  for (int j = start + slot; j < end; j += SLOTS) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(vh + (int64_t)j * D);
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    float p_nd = 0.f, p_dd = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float d0 = __uint_as_float(w[i] << 16) - vbl[2 * i];
+      const float d1 = __uint_as_float(w[i] & 0xffff0000u) - vbl[2 * i + 1];
+      p_nd = __builtin_fmaf(d0, d0, p_nd);
+      p_dd = __builtin_fmaf(d0, vbl[2 * i], p_dd);
+      p_nd = __builtin_fmaf(d1, d1, p_nd);
+      p_dd = __builtin_fmaf(d1, vbl[2 * i + 1], p_dd);
+    }
+#pragma unroll
+    for (int o = LPK / 2; o > 0; o >>= 1) {
+      p_nd += __shfl_xor(p_nd, o);
+      p_dd += __shfl_xor(p_dd, o);
+    }
+    if (lane == 0) {
+      nd[(int64_t)bh * stat_stride + j] = p_nd;
+      dd[(int64_t)bh * stat_stride + j] = p_dd;
+    }
+  }
+}
+
+// Block errors with the logits qbar_a . k_j on bf16 MFMAs (qbar in three exact bf16 pieces,
+// so the logits carry fp32-level accuracy). One workgroup per (head, key cluster, group of
+// 128 query centroids); wave w owns query centroids 32w..32w+31 of the group and keeps their
+// operand fragments in registers. The score tile is keys x centroids: a lane holds 16 keys
+// of ONE query centroid per 32-key block, so the block error accumulates lane-locally.
+template <int D, bool VALUE_AWARE>
+__global__ void __launch_bounds__(256)
+block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__ vbar, const bf16_t* __restrict__ kp,
+                        const int32_t* __restrict__ k_offsets, const float* __restrict__ sbar,
+                        const float* __restrict__ mrow, const float* __restrict__ nd, const float* __restrict__ dd,
+                        int64_t Nk, int64_t stat_stride, int Cq, int Ck, float scale, float* __restrict__ scores) {
+  constexpr int KSN = D / 16;
+  const int b = blockIdx.x, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+  const int ab = blockIdx.z * 4 + (threadIdx.x >> 6), nab = (Cq + 31) >> 5;
+  if (ab >= nab) return;
+  const int a = 32 * ab + li;
+  const bool live = a < Cq;
+  const int32_t* off = k_offsets + (int64_t)bh * (Ck + 2);
+  const int start = off[b], end = off[b + 1];
+  if (end <= start) {
+    if (live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + b] = 0.f;
+    return;
+  }
+  bf16x8 bq[3][KSN];
+  {
+    const bf16_t* src = q3 + (((int64_t)bh * nab + ab) * 3 * KSN) * 512 + lane * 8;
+#pragma unroll
+    for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+      for (int s = 0; s < KSN; ++s)
+        bq[pc][s] = as_bf16x8(*reinterpret_cast<const uint4*>(src + (pc * KSN + s) * 512));
+  }
+  const float m_a = live ? mrow[(int64_t)bh * Cq + a] : 0.f;
+  const float W = live ? __expf(fminf(sbar[((int64_t)bh * Cq + a) * Ck + b] - m_a, kMaxExponent)) : 0.f;
+  float nvb = 0.f;
+  if (VALUE_AWARE) {
+    const float* vb = vbar + ((int64_t)bh * Ck + b) * D;
+    for (int t = 0; t < D; ++t) nvb = __builtin_fmaf(vb[t], vb[t], nvb);
+  }
+  const bf16_t* kh = kp + (int64_t)bh * Nk * D;
+  const float* ndh = nd + (int64_t)bh * stat_stride;
+  const float* ddh = dd + (int64_t)bh * stat_stride;
+  float E = 0.f;
+  for (int j0 = start; j0 < end; j0 += 32) {
+    const int jr = min(j0 + li, end - 1);  // A operand: key row li of the block, dims 16s + 8lh..
+    const bf16_t* kr = kh + (int64_t)jr * D + 8 * lh;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KSN; ++s) {
+      const bf16x8 ak = as_bf16x8(*reinterpret_cast<const uint4*>(kr + 16 * s));
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[pc][s], acc, 0, 0, 0);
+    }
+    // register r is key j0 + 8(r/4) + 4lh + r%4, query centroid a
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int jb = j0 + 8 * g + 4 * lh;
+      float nn[4] = {0.f, 0.f, 0.f, 0.f}, dl[4] = {0.f, 0.f, 0.f, 0.f};
+      if (VALUE_AWARE) {  // arrays are padded past the last key; entries past `end` are unused
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          nn[r] = ndh[jb + r];
+          dl[r] = ddh[jb + r];
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (jb + r < end) {
+          const float w = __expf(fminf(acc[4 * g + r] * scale - m_a, kMaxExponent));
+          const float gdf = W - w;
+          if (VALUE_AWARE) {
+            E = __builtin_fmaf(gdf * gdf, nvb, E);
+            E = __builtin_fmaf(-2.0f * gdf * w, dl[r], E);
+            E = __builtin_fmaf(w * w, nn[r], E);
+          } else {
+            E = __builtin_fmaf(gdf, gdf, E);
+          }
+        }
+      }
+    }
+  }
+  E += __shfl_xor(E, 32);
+  if (live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + b] = E / (float)(end - start);
+}
+
 }  // namespace
 
 int run_probe(const float* qbar, const float* kbar, const float* vbar, const void* kp, const void* vp,
               svgear_dtype dt, const int32_t* k_offsets, int BH, int64_t Nk, int d, int Cq, int Ck, float scale,
-              bool value_aware, float* scores, float* sbar, float* mrow, hipStream_t s) {
+              bool value_aware, float* scores, float* sbar, float* mrow, bf16_t* q3, float* nd, float* dd,
+              hipStream_t s) {
+  const bool mfma = dt == SVGEAR_BF16;
+  const int rows = mfma ? (int)align_up(Cq, 32) : Cq;
   if (d == 64)
-    sbar_kernel<64><<<dim3(Cq, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow);
+    sbar_kernel<64><<<dim3(rows, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow,
+                                                   mfma ? q3 : nullptr);
   else
-    sbar_kernel<128><<<dim3(Cq, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow);
+    sbar_kernel<128><<<dim3(rows, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow,
+                                                    mfma ? q3 : nullptr);
   SVGEAR_LAUNCH_CHECK();
+  if (mfma) {
+    const int64_t stat_stride = probe_stat_stride(Nk);
+    const bf16_t* k16 = static_cast<const bf16_t*>(kp);
+    const bf16_t* v16 = static_cast<const bf16_t*>(vp);
+    const dim3 gs(Ck, BH), gb(Ck, BH, (unsigned)ceil_div(ceil_div(Cq, 32), 4));
+    if (value_aware) {
+      if (d == 64) value_stats_kernel<64><<<gs, 256, 0, s>>>(vbar, v16, k_offsets, Nk, stat_stride, Ck, nd, dd);
+      else value_stats_kernel<128><<<gs, 256, 0, s>>>(vbar, v16, k_offsets, Nk, stat_stride, Ck, nd, dd);
+      SVGEAR_LAUNCH_CHECK();
+    }
+#define SVGEAR_PM(D, VA)                                                                                     \
+  block_error_mfma_kernel<D, VA><<<gb, 256, 0, s>>>(q3, vbar, k16, k_offsets, sbar, mrow, nd, dd, Nk, stat_stride, \
+                                                    Cq, Ck, scale, scores)
+    if (d == 64) { if (value_aware) SVGEAR_PM(64, true); else SVGEAR_PM(64, false); }
+    else { if (value_aware) SVGEAR_PM(128, true); else SVGEAR_PM(128, false); }
+#undef SVGEAR_PM
+    SVGEAR_LAUNCH_CHECK();
+    return SVGEAR_OK;
+  }
   const int threads = Cq >= 256 ? 256 : (int)align_up(Cq, 64);
   dim3 grid(Ck, BH, (unsigned)ceil_div(Cq, 256));
 #define SVGEAR_PB(T, D, VA)                                                                                   \
   block_error_kernel<T, D, VA><<<grid, threads, 0, s>>>(qbar, vbar, static_cast<const T*>(kp),                \
                                                         static_cast<const T*>(vp), k_offsets, sbar, mrow, Nk, \
                                                         Cq, Ck, scale, scores)
-  if (dt == SVGEAR_F32) {
-    if (d == 64) { if (value_aware) SVGEAR_PB(float, 64, true); else SVGEAR_PB(float, 64, false); }
-    else { if (value_aware) SVGEAR_PB(float, 128, true); else SVGEAR_PB(float, 128, false); }
-  } else {
-    if (d == 64) { if (value_aware) SVGEAR_PB(bf16_t, 64, true); else SVGEAR_PB(bf16_t, 64, false); }
-    else { if (value_aware) SVGEAR_PB(bf16_t, 128, true); else SVGEAR_PB(bf16_t, 128, false); }
-  }
+  if (d == 64) { if (value_aware) SVGEAR_PB(float, 64, true); else SVGEAR_PB(float, 64, false); }
+  else { if (value_aware) SVGEAR_PB(float, 128, true); else SVGEAR_PB(float, 128, false); }
 #undef SVGEAR_PB
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;

@@ -14,7 +14,8 @@ namespace svgear {
 
 int run_probe(const float* qbar, const float* kbar, const float* vbar, const void* kp, const void* vp,
               svgear_dtype dt, const int32_t* k_offsets, int BH, int64_t Nk, int d, int Cq, int Ck, float scale,
-              bool value_aware, float* scores, float* sbar, float* mrow, hipStream_t s);
+              bool value_aware, float* scores, float* sbar, float* mrow, bf16_t* q3, float* nd, float* dd,
+              hipStream_t s);
 
 namespace {
 
@@ -174,10 +175,11 @@ build_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_off
 using namespace svgear;
 
 extern "C" size_t svgear_probe_route_workspace(int B, int H, int64_t Nk, int d, int Cq, int Ck) {
-  (void)Nk; (void)d;
-  if (B <= 0 || H <= 0 || Cq <= 0 || Ck <= 0) return 0;
+  if (B <= 0 || H <= 0 || Cq <= 0 || Ck <= 0 || Nk <= 0 || d <= 0) return 0;
   const size_t BH = (size_t)B * H;
-  return align_up(BH * Cq * Ck * 4, 256) + align_up(BH * Cq * 4, 256) + align_up(BH * (Cq + 1) * 8, 256);
+  return align_up(BH * Cq * Ck * 4, 256) + align_up(BH * Cq * 4, 256) + align_up(BH * (Cq + 1) * 8, 256) +
+         // bf16 probe: qbar in three bf16 pieces (operand order), per-key value statistics
+         align_up(BH * align_up(Cq, 32) * d * 3 * 2, 256) + 2 * align_up(BH * probe_stat_stride(Nk) * 4, 256);
 }
 
 extern "C" int svgear_probe_route(const float* qbar, const float* kbar, const float* vbar, const void* kp,
@@ -203,10 +205,14 @@ extern "C" int svgear_probe_route(const float* qbar, const float* kbar, const fl
   float* sbar = w.take<float>((size_t)BH * Cq * Ck);
   float* mrow = w.take<float>((size_t)BH * Cq);
   uint64_t* kstar = w.take<uint64_t>((size_t)BH * (Cq + 1));
+  bf16_t* q3 = w.take<bf16_t>((size_t)BH * align_up(Cq, 32) * (d > 0 ? d : 1) * 3);
+  float* nd = w.take<float>((size_t)BH * probe_stat_stride(Nk));
+  float* dd = w.take<float>((size_t)BH * probe_stat_stride(Nk));
+  if (!w.ok()) return SVGEAR_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!given) {
     int rc = run_probe(qbar, kbar, vbar, kp, vp, dt, k_offsets, BH, Nk, d, Cq, Ck, scale,
-                       !(flags & SVGEAR_PROBE_PLAIN), scores, sbar, mrow, s);
+                       !(flags & SVGEAR_PROBE_PLAIN), scores, sbar, mrow, q3, nd, dd, s);
     if (rc != SVGEAR_OK) return rc;
   }
   const int per_row = (flags & SVGEAR_ROUTE_PER_ROW) ? 1 : 0;
