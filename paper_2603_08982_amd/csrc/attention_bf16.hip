@@ -374,6 +374,13 @@ __device__ __forceinline__ float dot2_ones(uint32_t pair, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(x.b, one.b, acc, false);
 }
 
+// value held by lane ^ 32 (v_permlane32_swap: a VALU exchange of the two wave halves, no LDS)
+__device__ __forceinline__ float swap32(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16* lds_v4i16_ptr;
 
@@ -538,7 +545,9 @@ attn_bf16_d128_kernel(AttnArgs p) {
 
   // per-lane LDS byte offsets of the MFMA operands
   // K row li of a 32-row block, dims 16s + 8lh .. +7: chunk (2s + lh) ^ (li % 16)
-  const int koff0 = li * 256 + ((lh ^ (li & 15)) << 4);  // s = 0; other s: koff0 ^ (s << 5)
+  int koff[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) koff[s] = li * 256 + (((2 * s + lh) ^ (li & 15)) << 4);
   int voff[DB];  // transpose read: group = lane/16 -> (dim half, key half); r = lane%16
   {
     const int r = lane & 15, g = lane >> 4, ddhalf = g & 1, khalf = g >> 1;
@@ -598,7 +607,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
       bf16x8 ak[2 * KS];
 #pragma unroll
       for (int i = 0; i < 2 * KS; ++i)
-        ak[i] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (i & 1) * 32 * 256 + (koff0 ^ ((i >> 1) << 5))));
+        ak[i] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (i & 1) * 32 * 256 + koff[i >> 1]));
 #pragma unroll
       for (int i = 0; i < 2 * KS; ++i)
         sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[i], bq[i >> 1], sacc[i & 1], 0, 0, 0);
@@ -617,7 +626,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
       float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = fmaxf(mx, swap32(mx));
       const float ms = mx * c;
       if (__any(ms > m + kLazyRescale)) rescale(fmaxf(m, ms));
       const float neg_m = -m;
@@ -644,7 +653,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sacc[kb][4 * g + r]);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = fmaxf(mx, swap32(mx));
       if (__any(mx > m + kLazyRescale)) rescale(fmaxf(m, mx));
       const float m_use = (m == -INFINITY) ? 0.f : m;
 #pragma unroll
@@ -725,7 +734,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
 
   // ---- epilogue: lane holds query li, dims 32db + 8g + 4lh + 0..3
   if (wave_active) {
-    const float lt = l + __shfl_xor(l, 32);
+    const float lt = l + swap32(l);
     if (qvalid) {
       const float inv = lt > 0.f ? 1.0f / lt : 0.f;
       bf16_t* o = static_cast<bf16_t*>(p.op) + ((int64_t)bh * p.Nq + qrow) * D;
