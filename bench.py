@@ -42,6 +42,12 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense brackets")
     ap.add_argument("--sample-rows", type=int, default=96, help="output rows checked against the oracle")
+    ap.add_argument("--mode", default="layer", choices=["layer", "sweep", "trajectory"],
+                    help="layer: one JSON line for the whole hot path (default); sweep: routed-budget sweep with "
+                         "per-stage times and the compensation-only / dense brackets; trajectory: warm-started "
+                         "k-means over denoising steps")
+    ap.add_argument("--layers", type=int, default=40, help="trajectory mode: attention layers per step")
+    ap.add_argument("--traj-steps", type=int, default=10, help="trajectory mode: denoising steps")
     return ap.parse_args()
 
 
@@ -163,6 +169,98 @@ def cpu_baseline(orc, wl, Q, K, V, cq0, ck0, budget, n_rows=48):
     }
 
 
+def _time_ms(fn, reps=3):
+    best = None
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = fn()
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1)
+        best = t if best is None else min(best, t)
+    return best, out
+
+
+def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
+    """Budget sweep on one clustering: per-stage times, compensation-only and dense brackets."""
+    cq, ck = cq0.clone(), ck0.clone()
+    scale = float(wl.d) ** -0.5
+    tm = StageTimer()
+    r = run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, 0, tm)  # warm-up
+    tm = StageTimer()
+    r = run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, 0, tm)
+    torch.cuda.synchronize()
+    base = tm.stages_ms()
+    dense_flops = 4.0 * wl.B * wl.H * float(wl.N) ** 2 * wl.d
+    rows = []
+    for rho in [0.0, 0.05, 0.10, 0.15, 0.25, 0.50, 1.0]:
+        from workloads import budget_pairs
+        budget = budget_pairs(rho, wl.N, wl.N)
+        t_pr, pr = _time_ms(lambda: sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], budget,
+                                                   scale))
+        t_at, _ = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
+                                                       pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale))
+        dens = float(pr["routed_cost"].sum().item()) / (wl.B * wl.H * float(wl.N) ** 2)
+        rows.append({"rho": rho, "achieved_density": dens, "probe_route_ms": t_pr, "attention_ms": t_at,
+                     "layer_ms": base["kmeans"] + base["permute"] + base["unpermute"] + t_pr + t_at,
+                     "attention_routed_tflops": 4.0 * wl.d * float(pr["routed_cost"].sum().item()) / (t_at * 1e-3) / 1e12})
+    out = {"mode": "sweep", "workload": wl.name, "kmeans_ms": base["kmeans"], "permute_ms": base["permute"],
+           "unpermute_ms": base["unpermute"], "sweep": rows}
+    try:
+        t_sd, _ = _time_ms(lambda: torch.nn.functional.scaled_dot_product_attention(Q, K, V), reps=2)
+        out["torch_sdpa_dense_ms"] = t_sd
+        out["torch_sdpa_dense_tflops"] = dense_flops / (t_sd * 1e-3) / 1e12
+    except Exception as ex:  # noqa: BLE001
+        out["torch_sdpa_error"] = str(ex)[:200]
+    print(json.dumps(out))
+
+
+def run_trajectory(sv, args, wl):
+    """Denoising-trajectory stack: `layers` attention layers x `traj_steps` steps; each step's
+    Q/K/V = previous + N(0, 0.05^2) drift (re-rounded to bf16); k-means warm-started from the
+    previous step's centroids with 2 iterations (step 0: seeded cold start, also 2 iterations);
+    routed budget 20 %. Reports the summed all-stage time of the layers per step."""
+    from workloads import make_qkv, kmeans_init_indices, budget_pairs
+    dev = torch.device("cuda:0")
+    wl = wl.with_(rho=0.20 if args.rho < 0 else args.rho, iters=2 if args.iters < 0 else args.iters)
+    budget = budget_pairs(wl.rho, wl.N, wl.N)
+    nv = wl.N - wl.n_tail
+    layers = []
+    for ell in range(args.layers):
+        w_l = wl.with_(seed=wl.seed + 1000 + ell)
+        Q, K, V = make_qkv(w_l, dev)
+        cq = torch.empty(wl.B, wl.H, wl.Cq, wl.d, device=dev)
+        ck = torch.empty(wl.B, wl.H, wl.Ck, wl.d, device=dev)
+        for h in range(wl.H):
+            cq[0, h] = Q[0, h][torch.from_numpy(kmeans_init_indices(w_l.seed, h, 0, nv, wl.Cq)).to(dev)].float()
+            ck[0, h] = K[0, h][torch.from_numpy(kmeans_init_indices(w_l.seed, h, 1, nv, wl.Ck)).to(dev)].float()
+        layers.append([Q, K, V, cq, ck])
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(12345)
+    per_step = []
+    for step in range(args.traj_steps):
+        if step > 0:
+            for Lr in layers:
+                for X in Lr[:3]:
+                    for h in range(wl.H):  # per head to bound temporaries
+                        X[0, h] = (X[0, h].float() + 0.05 * torch.randn(X[0, h].shape, generator=gen, device=dev)).to(X.dtype)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for Q, K, V, cq, ck in layers:
+            sv.attention_layer(Q, K, V, cq, ck, wl.iters, budget, wl.n_tail)  # centroids updated in place
+        e1.record()
+        torch.cuda.synchronize()
+        per_step.append(e0.elapsed_time(e1))
+    dense_flops = 4.0 * wl.B * wl.H * float(wl.N) ** 2 * wl.d * args.layers
+    warm = per_step[1:] if len(per_step) > 1 else per_step
+    print(json.dumps({"mode": "trajectory", "workload": wl.name, "layers": args.layers, "steps": args.traj_steps,
+                      "kmeans_iters_per_step": wl.iters, "rho": wl.rho, "attention_ms_per_step": per_step,
+                      "mean_ms_per_warm_step": sum(warm) / len(warm),
+                      "dense_equiv_tflops_warm": dense_flops / (sum(warm) / len(warm) * 1e-3) / 1e12}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -183,6 +281,9 @@ def main():
     if args.iters > 0: wl = wl.with_(iters=args.iters)
     budget = budget_pairs(wl.rho, wl.N, wl.N)
 
+    if args.mode == "trajectory":
+        run_trajectory(sv, args, wl)
+        return
     Q, K, V = make_qkv(wl, dev)
     nv = wl.N - wl.n_tail
     cq0 = torch.empty(wl.B, wl.H, wl.Cq, wl.d, device=dev)
@@ -193,6 +294,9 @@ def main():
             ik = torch.from_numpy(kmeans_init_indices(wl.seed, b * wl.H + h, 1, nv, wl.Ck)).to(dev)
             cq0[b, h] = Q[b, h][iq].float()
             ck0[b, h] = K[b, h][ik].float()
+    if args.mode == "sweep":
+        run_sweep(sv, args, wl, Q, K, V, cq0, ck0)
+        return
     cq, ck = cq0.clone(), ck0.clone()
 
     for _ in range(args.warmup):
