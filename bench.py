@@ -28,6 +28,9 @@ import torch  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the fused attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
+# 1 GiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); only known for the default configuration of a workload.
+MEASURED_ATTENTION_TRAFFIC_BYTES = {("wan", 0.25): 48.74e9}
 
 
 def parse():
@@ -46,6 +49,9 @@ def parse():
                     help="layer: one JSON line for the whole hot path (default); sweep: routed-budget sweep with "
                          "per-stage times and the compensation-only / dense brackets; trajectory: warm-started "
                          "k-means over denoising steps")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE run can be scaled against it")
     ap.add_argument("--layers", type=int, default=40, help="trajectory mode: attention layers per step")
     ap.add_argument("--traj-steps", type=int, default=10, help="trajectory mode: denoising steps")
     return ap.parse_args()
@@ -299,6 +305,12 @@ def main():
         return
     cq, ck = cq0.clone(), ck0.clone()
 
+    if args.traffic_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget)
     torch.cuda.synchronize()
@@ -355,7 +367,8 @@ def main():
         "attention_stage": {"ms": attn_ms, "dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if wl.dtype == "bf16" else "attn_f32_kernel",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get((wl.name, wl.rho)) if wl.H == 40 else None,
                      "algorithmic_flops_per_launch": attn_flops},
     }
 
