@@ -404,6 +404,14 @@ __device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_ad
                : "v"(gptr), "s"(lds_addr)
                : "memory", "m0");
 }
+// Same copy with the global address given as a wave-uniform base plus a 32-bit byte offset
+// per lane (no 64-bit vector arithmetic).
+__device__ __forceinline__ void async_copy_16B(const void* gbase, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+               :
+               : "v"(byte_off), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)(p);
 }
@@ -524,23 +532,42 @@ attn_bf16_d128_kernel(AttnArgs p) {
     }
   };
 
-  // one wave-wide copy moves rows 4*inst .. 4*inst+3 of a tile; lane -> (row, LDS chunk slot)
+  // one wave-wide copy moves rows 4*inst .. 4*inst+3 of a tile; lane -> (row, LDS chunk slot).
+  // Copy i of this wave is instruction inst = wave + i*NW of the tile: its tile row, the
+  // swizzled 16-byte chunk it fetches and its LDS destination do not depend on the tile.
+  constexpr int CPW = INST_PER_TILE / NW;  // copies per tensor per wave per tile
   const int cp_row = lane >> 4, cp_slot = lane & 15;
   const uint32_t lds_k0 = lds_address(Ks), lds_v0 = lds_address(Vs);
-  auto issue_loads = [&](int t) {
+  int cp_rr[CPW];
+  uint32_t cp_koff[CPW], cp_voff[CPW];
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    cp_rr[i] = 4 * (wave + i * NW) + cp_row;
+    cp_koff[i] = (uint32_t)((cp_slot ^ (cp_rr[i] & 15)) << 4);
+    cp_voff[i] = (uint32_t)((cp_slot ^ ((cp_rr[i] & 3) << 2)) << 4);
+  }
+  // permuted rows (of K/V or of the centroid tables) this lane copies for tile t
+  auto fetch_rows = [&](int t, int (&rows)[CPW]) {
+    const int32_t* rm = rowmap + (t % RS) * BN;
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) rows[i] = rm[cp_rr[i]];
+  };
+  auto issue_copies = [&](int t, const int (&rows)[CPW]) {
     const bf16_t* kb = t < nt_r ? kh : kc;
     const bf16_t* vb = t < nt_r ? vh : vc;
-    const int32_t* rm = rowmap + (t % RS) * BN;
-    const uint32_t kdst = lds_k0 + (t % NSTAGE) * TILE_BYTES;
-    const uint32_t vdst = lds_v0 + (t % NSTAGE) * TILE_BYTES;
+    const uint32_t kdst = lds_k0 + (t % NSTAGE) * TILE_BYTES + wave * 1024;
+    const uint32_t vdst = lds_v0 + (t % NSTAGE) * TILE_BYTES + wave * 1024;
 #pragma unroll
-    for (int i = 0; i < INST_PER_TILE / NW; ++i) {
-      const int inst = wave + i * NW;
-      const int rr = 4 * inst + cp_row;
-      const int64_t grow = (int64_t)rm[rr] * D;
-      async_copy_16B(kb + grow + ((cp_slot ^ (rr & 15)) << 3), __builtin_amdgcn_readfirstlane(kdst + inst * 1024));
-      async_copy_16B(vb + grow + ((cp_slot ^ ((rr & 3) << 2)) << 3), __builtin_amdgcn_readfirstlane(vdst + inst * 1024));
+    for (int i = 0; i < CPW; ++i) {
+      const uint32_t rowoff = (uint32_t)rows[i] * (D * 2);
+      async_copy_16B(kb, rowoff + cp_koff[i], __builtin_amdgcn_readfirstlane(kdst + i * NW * 1024));
+      async_copy_16B(vb, rowoff + cp_voff[i], __builtin_amdgcn_readfirstlane(vdst + i * NW * 1024));
     }
+  };
+  auto issue_loads = [&](int t) {
+    int rows[CPW];
+    fetch_rows(t, rows);
+    issue_copies(t, rows);
   };
 
   // per-lane LDS byte offsets of the MFMA operands
@@ -590,7 +617,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
   // One 64-key tile for this wave's 32 queries. BIASED = false: a full routed tile.
   // BIASED = true: per-key additive bias (ragged routed tile: 0 / -inf; compensation tile:
   // log2|k_b| or -inf).
-  auto compute_tile = [&](int t, auto biased_tag) {
+  auto compute_tile = [&](int t, auto biased_tag, auto&& after_scores) {
     constexpr bool BIASED = decltype(biased_tag)::value;
     const unsigned char* Kb = Ks + (t % NSTAGE) * TILE_BYTES;
     const unsigned char* Vb = Vs + (t % NSTAGE) * TILE_BYTES;
@@ -619,13 +646,22 @@ attn_bf16_d128_kernel(AttnArgs p) {
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
+    after_scores();
     // ---- online softmax in the base-2 domain; the running maximum m is refreshed lazily
     // (only when a score exceeds it by more than 2^kLazyRescale), so O is rarely rescaled
     uint32_t pk[2][8];
     if constexpr (!BIASED) {
-      float mx = fmaxf(sacc[0][0], sacc[1][0]);
+      // four independent max chains (a single chain of 16 dependent ops stalls the wave)
+      float mxa = fmaxf(sacc[0][0], sacc[1][0]), mxb = fmaxf(sacc[0][1], sacc[1][1]);
+      float mxc = fmaxf(sacc[0][2], sacc[1][2]), mxd = fmaxf(sacc[0][3], sacc[1][3]);
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][r]), sacc[1][r]);
+      for (int r = 4; r < 16; r += 4) {
+        mxa = fmaxf(fmaxf(mxa, sacc[0][r]), sacc[1][r]);
+        mxb = fmaxf(fmaxf(mxb, sacc[0][r + 1]), sacc[1][r + 1]);
+        mxc = fmaxf(fmaxf(mxc, sacc[0][r + 2]), sacc[1][r + 2]);
+        mxd = fmaxf(fmaxf(mxd, sacc[0][r + 3]), sacc[1][r + 3]);
+      }
+      float mx = fmaxf(fmaxf(mxa, mxb), fmaxf(mxc, mxd));
       mx = fmaxf(mx, swap32(mx));
       const float ms = mx * c;
       if (__any(ms > m + kLazyRescale)) rescale(fmaxf(m, ms));
@@ -665,11 +701,21 @@ attn_bf16_d128_kernel(AttnArgs p) {
           pk[kb][r >> 1] = pack_bf16(p0, p1);
         }
     }
-    // row sums from the bf16-rounded probabilities (the values the PV product uses)
+    // row sums from the bf16-rounded probabilities (the values the PV product uses), in
+    // four independent partial sums
+    {
+      float l0 = 0.f, l1 = 0.f, l2 = 0.f, l3 = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) l = dot2_ones(pk[kb][u], l);
+        for (int u = 0; u < 8; u += 4) {
+          l0 = dot2_ones(pk[kb][u], l0);
+          l1 = dot2_ones(pk[kb][u + 1], l1);
+          l2 = dot2_ones(pk[kb][u + 2], l2);
+          l3 = dot2_ones(pk[kb][u + 3], l3);
+        }
+      l += (l0 + l1) + (l2 + l3);
+    }
     // ---- O^T += V^T P^T : k-step ks covers keys 16ks .. 16ks+15; the transpose reads of
     // k-step ks+1 are issued before the MFMAs of k-step ks
     {
@@ -697,14 +743,18 @@ attn_bf16_d128_kernel(AttnArgs p) {
     }
   };
 
-  // pipeline step around the compute of tile t
-  auto step_begin = [&](int t) {
-    if (t + NSTAGE - 1 < T) issue_loads(t + NSTAGE - 1);
-  };
-  auto step_end = [&](int t) {
+  // pipeline step around the compute of tile t: the rows of tile t+NSTAGE-1 are looked up
+  // first, its copies are issued once the score MFMAs are in flight (the copies have tiles
+  // of slack; the wave should not stall on the row lookup before feeding the matrix cores)
+  auto run_tile = [&](int t, auto biased_tag) {
+    const bool more = t + NSTAGE - 1 < T;
+    int rows[CPW];
+    if (more) fetch_rows(t + NSTAGE - 1, rows);
+    if (wave_active) compute_tile(t, biased_tag, [&] { if (more) issue_copies(t + NSTAGE - 1, rows); });
+    else if (more) issue_copies(t + NSTAGE - 1, rows);
     if (t + NSTAGE < T) map_tile(t + NSTAGE);
     // this wave's copies of tile t+1 must have landed; younger tiles may stay in flight
-    if (t + NSTAGE - 1 < T) SVGEAR_WAIT_VMCNT((NSTAGE - 2) * LOADS_PER_TILE);
+    if (more) SVGEAR_WAIT_VMCNT((NSTAGE - 2) * LOADS_PER_TILE);
     else SVGEAR_WAIT_VMCNT(0);
     __syncthreads();
   };
@@ -721,16 +771,8 @@ attn_bf16_d128_kernel(AttnArgs p) {
   else SVGEAR_WAIT_VMCNT(0);
   __syncthreads();
 
-  for (int t = 0; t < nt_full; ++t) {
-    step_begin(t);
-    if (wave_active) compute_tile(t, std::false_type{});
-    step_end(t);
-  }
-  for (int t = nt_full; t < T; ++t) {
-    step_begin(t);
-    if (wave_active) compute_tile(t, std::true_type{});
-    step_end(t);
-  }
+  for (int t = 0; t < nt_full; ++t) run_tile(t, std::false_type{});
+  for (int t = nt_full; t < T; ++t) run_tile(t, std::true_type{});
 
   // ---- epilogue: lane holds query li, dims 32db + 8g + 4lh + 0..3
   if (wave_active) {
