@@ -282,16 +282,20 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   constexpr int COPIES = CHUNK_BYTES / 1024 / kFilterWaves;
   static_assert(CHUNK_BYTES % (1024 * kFilterWaves) == 0, "chunk copies must split over the waves");
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
-  float* cns = reinterpret_cast<float*>(smem + 2 * CHUNK_BYTES);  // [2][kCentChunk]
-  float* red = cns + 2 * kCentChunk;                              // [64 * kFilterWaves]
+  float* cns = reinterpret_cast<float*>(smem + 2 * CHUNK_BYTES);  // [Cpad] |c|^2 of every centroid
+  float* red = cns + Cpad;                                        // [64 * kFilterWaves]
   const int bh = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const float* cnb = cn + (int64_t)bh * Cpad;
 
-  // Cm^2 = max |c|^2 over the real centroids
+  // |c|^2 table into LDS; Cm^2 = max |c|^2 over the real centroids
   float cm2 = 0.f;
-  for (int c = tid; c < C; c += 64 * kFilterWaves) cm2 = fmaxf(cm2, cnb[c]);
+  for (int c = tid; c < Cpad; c += 64 * kFilterWaves) {
+    const float v = cnb[c];
+    cns[c] = v;
+    if (c < C) cm2 = fmaxf(cm2, v);
+  }
   red[tid] = cm2;
   __syncthreads();
   for (int w = 32 * kFilterWaves; w > 0; w >>= 1) {
@@ -328,50 +332,69 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
 
   float best[2] = {INFINITY, INFINITY}, second[2] = {INFINITY, INFINITY};
   int arg[2] = {0, 0};
+
+  // Software pipeline over 32-centroid blocks g = 0 .. 2 nchunks - 1 (block g lives in LDS
+  // stage (g/2)&1): while the VALU ranks the scores of block g, the matrix cores already
+  // accumulate block g+1. The slices are written in issue order and fenced, because a wave
+  // blocks at its next MFMA while the matrix core is busy: VALU work overlaps only if it sits
+  // between the MFMAs in program order.
+  //   slice i of a step: the two MFMAs of operand fragment i of block g+1 (one per row set),
+  //                      then the score / best / second-best update of register i of block g.
+  f32x16 accA0, accA1, accB0, accB1;  // two block accumulators per row set, used alternately
+  auto block_base = [&](int g) { return smem + ((g >> 1) & 1) * CHUNK_BYTES + (g & 1) * (2 * KSN * 1024) + lane * 16; };
+  auto rank_slice = [&](int g, int r, const f32x16& a0, const f32x16& a1) {
+    // register r of block g is centroid 32 g + 8(r/4) + 4 lh + r%4, row li of the set
+    const int idx = 32 * g + 8 * (r >> 2) + 4 * lh + (r & 3);
+    const float nn = cns[idx];
+    const float s0 = __builtin_fmaf(-2.0f, a0[r], nn);
+    const float s1 = __builtin_fmaf(-2.0f, a1[r], nn);
+    second[0] = __builtin_amdgcn_fmed3f(s0, best[0], second[0]);
+    second[1] = __builtin_amdgcn_fmed3f(s1, best[1], second[1]);
+    if (s0 < best[0]) { best[0] = s0; arg[0] = idx; }
+    if (s1 < best[1]) { best[1] = s1; arg[1] = idx; }
+  };
+  // one pipeline step: MFMAs of block g+1 (if any) interleaved with the ranking of block g
+  auto step = [&](int g, bool has_next, const f32x16& cur0, const f32x16& cur1, f32x16& nxt0, f32x16& nxt1) {
+    if (has_next) {
+      const unsigned char* nb = block_base(g + 1);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) nxt0[r] = nxt1[r] = 0.f;
+      bf16x8 a[2 * KSN];
+      a[0] = as_bf16x8(*reinterpret_cast<const uint4*>(nb));
+      a[1] = as_bf16x8(*reinterpret_cast<const uint4*>(nb + 1024));
+#pragma unroll
+      for (int i = 0; i < 2 * KSN; ++i) {
+        if (i + 2 < 2 * KSN) a[i + 2] = as_bf16x8(*reinterpret_cast<const uint4*>(nb + (i + 2) * 1024));
+        nxt0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bx[0][i % KSN], nxt0, 0, 0, 0);
+        nxt1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bx[1][i % KSN], nxt1, 0, 0, 0);
+        if (g >= 0 && i * 16 / (2 * KSN) < 16) {
+          // 16 registers spread over the 2 KSN slices
+#pragma unroll
+          for (int r = i * 16 / (2 * KSN); r < (i + 1) * 16 / (2 * KSN); ++r) rank_slice(g, r, cur0, cur1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) rank_slice(g, r, cur0, cur1);
+    }
+  };
+
+  // prologue: chunks 0 and 1 in flight, block 0 accumulated
   issue_chunk(0);
-  if (tid < kCentChunk) cns[tid] = cnb[tid];
+  if (nchunks > 1) issue_chunk(1);
   SVGEAR_WAIT_VMCNT(0);
   __syncthreads();
+  step(-1, true, accB0, accB1, accA0, accA1);  // accumulates block 0 into A (nothing to rank yet)
   for (int ch = 0; ch < nchunks; ++ch) {
-    float cn_next = 0.f;
-    if (ch + 1 < nchunks) {
-      issue_chunk(ch + 1);
-      if (tid < kCentChunk) cn_next = cnb[(ch + 1) * kCentChunk + tid];
-    }
-    const float* cnc = cns + (ch & 1) * kCentChunk;
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      // block layout in the stage: [piece][s][lane][8 bf16]
-      const unsigned char* cb = smem + (ch & 1) * CHUNK_BYTES + blk * (2 * KSN * 1024) + lane * 16;
-      f32x16 acc0, acc1;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.f;
-#pragma unroll
-      for (int ps = 0; ps < 2 * KSN; ++ps) {
-        const bf16x8 a = as_bf16x8(*reinterpret_cast<const uint4*>(cb + ps * 1024));
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[0][ps % KSN], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[1][ps % KSN], acc1, 0, 0, 0);
-      }
-      // register r is centroid 8(r/4) + 4 lh + r%4 of the block, row li of the set
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 n4 = *reinterpret_cast<const float4*>(cnc + 32 * blk + 8 * g + 4 * lh);
-        const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int idx = ch * kCentChunk + 32 * blk + 8 * g + 4 * lh + r;
-          const float s0 = __builtin_fmaf(-2.0f, acc0[4 * g + r], nn[r]);
-          const float s1 = __builtin_fmaf(-2.0f, acc1[4 * g + r], nn[r]);
-          second[0] = __builtin_amdgcn_fmed3f(s0, best[0], second[0]);
-          second[1] = __builtin_amdgcn_fmed3f(s1, best[1], second[1]);
-          if (s0 < best[0]) { best[0] = s0; arg[0] = idx; }
-          if (s1 < best[1]) { best[1] = s1; arg[1] = idx; }
-        }
-      }
-    }
-    if (ch + 1 < nchunks && tid < kCentChunk) cns[((ch + 1) & 1) * kCentChunk + tid] = cn_next;
+    // block 2ch+1 (same chunk) into B while ranking block 2ch from A
+    step(2 * ch, true, accA0, accA1, accB0, accB1);
+    // stage ch&1 is now free for chunk ch+2, and chunk ch+1 (issued one iteration ago) has landed
     SVGEAR_WAIT_VMCNT(0);
     __syncthreads();
+    if (ch + 2 < nchunks) issue_chunk(ch + 2);
+    // block 2ch+2 (next chunk) into A while ranking block 2ch+1 from B
+    step(2 * ch + 1, ch + 1 < nchunks, accB0, accB1, accA0, accA1);
   }
   constexpr float kappa = 1.52587890625e-05f + (2 * D + 1) * 1.1920928955078125e-07f + D * 5.9604644775390625e-08f;
 #pragma unroll
@@ -471,7 +494,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   auto assign = assign_mfma_kernel<T, D>;
   SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  const size_t lds_f = 2 * (size_t)kCentChunk * D * 4 + (2 * kCentChunk + 64 * kFilterWaves) * sizeof(float);
+  const size_t lds_f = 2 * (size_t)kCentChunk * D * 4 + ((size_t)Cpad + 64 * kFilterWaves) * sizeof(float);
   if constexpr (kFilter) {
     SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
