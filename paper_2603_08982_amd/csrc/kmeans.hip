@@ -342,10 +342,9 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   //                      then the score / best / second-best update of register i of block g.
   f32x16 accA0, accA1, accB0, accB1;  // two block accumulators per row set, used alternately
   auto block_base = [&](int g) { return smem + ((g >> 1) & 1) * CHUNK_BYTES + (g & 1) * (2 * KSN * 1024) + lane * 16; };
-  auto rank_slice = [&](int g, int r, const f32x16& a0, const f32x16& a1) {
+  auto rank_slice = [&](int g, int r, float nn, const f32x16& a0, const f32x16& a1) {
     // register r of block g is centroid 32 g + 8(r/4) + 4 lh + r%4, row li of the set
     const int idx = 32 * g + 8 * (r >> 2) + 4 * lh + (r & 3);
-    const float nn = cns[idx];
     const float s0 = __builtin_fmaf(-2.0f, a0[r], nn);
     const float s1 = __builtin_fmaf(-2.0f, a1[r], nn);
     second[0] = __builtin_amdgcn_fmed3f(s0, best[0], second[0]);
@@ -355,28 +354,38 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   };
   // one pipeline step: MFMAs of block g+1 (if any) interleaved with the ranking of block g
   auto step = [&](int g, bool has_next, const f32x16& cur0, const f32x16& cur1, f32x16& nxt0, f32x16& nxt1) {
+    // |c|^2 of the 16 centroids this lane ranks, fetched up front (no LDS wait inside the slices)
+    float nn[16];
+    if (g >= 0) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4*>(cns + 32 * g + 8 * q + 4 * lh);
+        nn[4 * q] = v.x; nn[4 * q + 1] = v.y; nn[4 * q + 2] = v.z; nn[4 * q + 3] = v.w;
+      }
+    }
     if (has_next) {
       const unsigned char* nb = block_base(g + 1);
 #pragma unroll
       for (int r = 0; r < 16; ++r) nxt0[r] = nxt1[r] = 0.f;
       bf16x8 a[2 * KSN];
-      a[0] = as_bf16x8(*reinterpret_cast<const uint4*>(nb));
-      a[1] = as_bf16x8(*reinterpret_cast<const uint4*>(nb + 1024));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = as_bf16x8(*reinterpret_cast<const uint4*>(nb + i * 1024));
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < 2 * KSN; ++i) {
-        if (i + 2 < 2 * KSN) a[i + 2] = as_bf16x8(*reinterpret_cast<const uint4*>(nb + (i + 2) * 1024));
+        if (i + 4 < 2 * KSN) a[i + 4] = as_bf16x8(*reinterpret_cast<const uint4*>(nb + (i + 4) * 1024));
         nxt0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bx[0][i % KSN], nxt0, 0, 0, 0);
         nxt1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bx[1][i % KSN], nxt1, 0, 0, 0);
-        if (g >= 0 && i * 16 / (2 * KSN) < 16) {
+        if (g >= 0) {
           // 16 registers spread over the 2 KSN slices
 #pragma unroll
-          for (int r = i * 16 / (2 * KSN); r < (i + 1) * 16 / (2 * KSN); ++r) rank_slice(g, r, cur0, cur1);
+          for (int r = i * 16 / (2 * KSN); r < (i + 1) * 16 / (2 * KSN); ++r) rank_slice(g, r, nn[r], cur0, cur1);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) rank_slice(g, r, cur0, cur1);
+      for (int r = 0; r < 16; ++r) rank_slice(g, r, nn[r], cur0, cur1);
     }
   };
 
