@@ -52,6 +52,14 @@ def test_kmeans_lockstep_video_bf16_with_tail():
     _lockstep(Q, wl.Cq, 2, seed=wl.seed, tensor_id=0)
 
 
+@pytest.mark.parametrize("name", ["mini_d64", "mini_manyq", "mini_f32_d128"])
+def test_kmeans_lockstep_other_shapes(name):
+    wl = get_workload(name)
+    Q, K, V = make_qkv(wl, dev())
+    _lockstep(Q, wl.Cq, 2, seed=wl.seed, tensor_id=0)
+    _lockstep(K, wl.Ck, 2, seed=wl.seed, tensor_id=1, X2=V)
+
+
 def test_kmeans_free_running_matches_oracle():
     wl = get_workload("tiny")
     Q, K, V = make_qkv(wl, dev())

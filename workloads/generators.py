@@ -59,6 +59,12 @@ WORKLOADS = {
     # Scaled-down video-shaped cases used by the parity tests (oracle runs them in seconds).
     "mini_video": Workload("mini_video", 1, 2, 6 * 10 * 16, 0, 128, 12, 40, 4, 0.25, "bf16", 32,
                            1.0, 0.3, (6, 10, 16), (2, 4, 4), 3),
+    # bf16 with d = 64 (the generic MFMA kernel), query clusters spanning several 128-row tiles
+    "mini_d64": Workload("mini_d64", 1, 2, 1500, 0, 64, 5, 37, 3, 0.3, "bf16", 8, 1.0, 0.3, None, None, 7),
+    # more query clusters than one probe workgroup covers (140 > 128), few key clusters
+    "mini_manyq": Workload("mini_manyq", 1, 2, 900, 0, 128, 140, 20, 3, 0.25, "bf16", 24, 1.0, 0.3, None, None, 9),
+    # fp32 with d = 128, batch of two
+    "mini_f32_d128": Workload("mini_f32_d128", 2, 1, 700, 0, 128, 9, 33, 3, 0.25, "f32", 12, 1.5, 0.4, None, None, 11),
     "mini_video_tail": Workload("mini_video_tail", 1, 2, 5 * 9 * 14 + 37, 37, 128, 10, 30, 4,
                                 0.25, "bf16", 32, 1.0, 0.3, (5, 9, 14), (2, 4, 4), 5),
 }
