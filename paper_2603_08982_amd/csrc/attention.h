@@ -24,6 +24,12 @@ struct AttnArgs {
   const int32_t* tile_a;
   const int32_t* tile_row0;
   const int32_t* n_tiles;
+  // work lists of the d = 128 bf16 kernel (see plan_d128): tiles sorted longest first and
+  // dealt to 8 lists, one per XCD; sched_x = [8] first slot, [8] tile count, [8] next counter
+  const int32_t* sched_bh;
+  const int32_t* sched_a;
+  const int32_t* sched_row0;
+  int32_t* sched_x;
   int64_t Nq, Nk;
   int BH, Cq, Ck, max_tiles;
   float scale;
@@ -38,6 +44,10 @@ __device__ __forceinline__ bool mask_bit(const uint32_t* mrow, int b) { return (
 constexpr int kBf16Waves = 4;
 // Query rows per workgroup tile of the bf16 kernel used for head dimension d.
 int attn_bf16_bm(int d);
+
+// Workspace of the d = 128 work lists (bytes) and their construction on stream s.
+size_t plan_d128_workspace(int BH, int Cq, int64_t Nq);
+int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s);
 
 // LDS bytes the bf16 kernel needs for head dimension d and Ck key clusters.
 size_t attn_bf16_lds_bytes(int d, int Ck);

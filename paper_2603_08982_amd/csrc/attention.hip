@@ -208,7 +208,8 @@ extern "C" size_t svgear_sparse_attn_comp_workspace(int B, int H, int64_t Nq, in
   if (B <= 0 || H <= 0 || Nq <= 0 || Cq <= 0 || Ck <= 0 || d <= 0) return 0;
   const size_t BH = (size_t)B * H;
   const size_t max_tiles = (size_t)ceil_div(Nq, 64) + Cq + 1;  // bound for either tile height
-  return 2 * align_up(BH * max_tiles * 4, 256) + align_up(BH * 4, 256) + 2 * align_up(BH * Ck * d * 2, 256);
+  return 2 * align_up(BH * max_tiles * 4, 256) + align_up(BH * 4, 256) + 2 * align_up(BH * Ck * d * 2, 256) +
+         plan_d128_workspace((int)BH, Cq, Nq);
 }
 
 extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
@@ -242,7 +243,8 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
   plan_kernel<<<BH, 256, (Cq + 2) * sizeof(int32_t), s>>>(q_offsets, Cq, BM, max_tiles, tile_a, tile_row0, n_tiles);
   SVGEAR_LAUNCH_CHECK();
   AttnArgs a{qp, kp, vp, kbar, vbar, kbar16, vbar16, q_offsets, k_offsets, mask_bits, row_ptr, col_idx,
-             tile_a, tile_row0, n_tiles, Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse};
+             tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr,
+             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse};
   if (dt == SVGEAR_F32) {
     dim3 grid(max_tiles, BH);
     if (d == 64)
@@ -258,6 +260,10 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
   to_bf16_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(vbar, n, vbar16);
   SVGEAR_LAUNCH_CHECK();
   if (attn_bf16_lds_bytes(d, Ck) > 160 * 1024) return SVGEAR_ERR_UNSUPPORTED;
+  if (d == 128) {
+    const int rc = plan_d128(a, static_cast<char*>(ws) + w.used, ws_bytes - w.used, s);
+    if (rc != SVGEAR_OK) return rc;
+  }
   const unsigned total = (unsigned)align_up((size_t)BH * max_tiles, 8);
   return launch_attn_bf16(a, d, total, s);
 }

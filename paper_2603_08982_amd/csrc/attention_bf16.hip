@@ -412,6 +412,13 @@ __device__ __forceinline__ void async_copy_16B(const void* gbase, uint32_t byte_
                : "v"(byte_off), "s"(gbase), "s"(lds_addr)
                : "memory", "m0");
 }
+// A wave-uniform pointer the compiler could not prove uniform, moved to scalar registers.
+__device__ __forceinline__ const void* uniform_ptr(const void* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)(p);
 }
@@ -419,17 +426,18 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 static inline size_t lds_bytes_d128(int Ck, int stages) {
   const size_t kv = (size_t)stages * 2 * BN * 128 * 2;  // K and V, `stages` buffers each
   const size_t lw = (size_t)align_up(Ck, 64) * 4;
-  const size_t seg = (size_t)(2 * (Ck + 1) + 1) * 4;
+  const size_t seg = (size_t)(2 * (Ck + 2) + 1) * 4;  // vstart, pstart, claimed tile slot
   return kv + (size_t)(stages + 2) * BN * 4 + lw + align_up(seg, 16);
 }
 
 // vmcnt(n) with expcnt and lgkmcnt left unconstrained (gfx9 s_waitcnt encoding)
 #define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-// NW waves of 32 query rows; NSTAGE K/V tile buffers (tile t+NSTAGE-1 is in flight while
-// tile t is computed).
-template <int NW, int NSTAGE>
-__global__ void __launch_bounds__(64 * NW, 8 / NW)
+// NW waves of 32 query rows (three per SIMD); NSTAGE K/V tile buffers. The first CW waves of
+// the workgroup issue the tile copies, after their compute of the step (just before the tile
+// barrier): measured faster than issuing them behind the score MFMAs or from all waves.
+template <int NW, int NSTAGE, int CW>
+__global__ void __launch_bounds__(64 * NW, 1)
 attn_bf16_d128_kernel(AttnArgs p) {
   constexpr int D = 128;
   constexpr int NT = 64 * NW;
@@ -437,9 +445,9 @@ attn_bf16_d128_kernel(AttnArgs p) {
   constexpr int DB = D / 32;
   constexpr int TILE_BYTES = BN * D * 2;            // 16 KB
   constexpr int INST_PER_TILE = TILE_BYTES / 1024;  // wave-wide 1 KB copies per tensor tile
-  constexpr int LOADS_PER_TILE = 2 * INST_PER_TILE / NW;  // copy instructions per wave per tile
+  constexpr int LOADS_PER_TILE = 2 * INST_PER_TILE / CW;  // copy instructions per copying wave per tile
   constexpr int RS = NSTAGE + 1;                    // row-map ring
-  static_assert(INST_PER_TILE % NW == 0, "copies must split evenly over the waves");
+  static_assert(INST_PER_TILE % CW == 0 && CW <= NW, "copies must split evenly over the copying waves");
 
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
   unsigned char* Ks = smem;                        // [NSTAGE][64 rows][256 B], chunk-swizzled
@@ -450,17 +458,32 @@ attn_bf16_d128_kernel(AttnArgs p) {
   int32_t* vstart = reinterpret_cast<int32_t*>(rag_bias + BN);
   int32_t* pstart = vstart + (p.Ck + 2);
 
-  const int total = gridDim.x;
-  const int wg = blockIdx.x;
-  const int logical = (wg & 7) * (total >> 3) + (wg >> 3);
-  const int bh = logical / p.max_tiles, tile = logical % p.max_tiles;
-  if (bh >= p.BH || tile >= p.n_tiles[bh]) return;
-
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // Every workgroup claims one tile: the next of the work list of the XCD it runs on (tiles
+  // of one query cluster are neighbours in a list, so the CUs of an XCD work on the same
+  // routed K/V at the same time and share it in their L2), or, once that list is used up, of
+  // the other XCDs' lists. Lists are sorted longest tile first and workgroups start in
+  // order, so the long tiles start early and the short ones fill the end of the launch. The
+  // grid covers the tile-count bound; workgroups that find every list used up exit.
+  int32_t* slot_s = pstart + (p.Ck + 2);
+  if (tid == 0) {
+    const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7;  // XCC_ID
+    int found = -1;
+    for (int xk = 0; xk < 8 && found < 0; ++xk) {
+      const int xl = (my_xcd + xk) & 7;
+      if (p.sched_x[16 + xl] >= p.sched_x[8 + xl]) continue;  // used up (the counter only grows)
+      const int slot = atomicAdd(p.sched_x + 16 + xl, 1);
+      if (slot < p.sched_x[8 + xl]) found = p.sched_x[xl] + slot;
+    }
+    *slot_s = found;
+  }
+  __syncthreads();
+  const int claimed = __builtin_amdgcn_readfirstlane(*slot_s);
+  if (claimed < 0) return;
+  const int bh = p.sched_bh[claimed], a = p.sched_a[claimed], row0 = p.sched_row0[claimed];
   const int Cq = p.Cq, Ck = p.Ck, R = Cq + 1, Cc = Ck + 1, W = (Cc + 31) / 32;
-  const int a = p.tile_a[(int64_t)bh * p.max_tiles + tile];
-  const int row0 = p.tile_row0[(int64_t)bh * p.max_tiles + tile];
   const int32_t* qo = p.q_offsets + (int64_t)bh * (Cq + 2);
   const int32_t* ko = p.k_offsets + (int64_t)bh * (Ck + 2);
   const int row_end = qo[a + 1];
@@ -500,7 +523,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
     lw[b] = v;
   }
   __syncthreads();
-  const int n_r = vstart[ne];
+  const int n_r = __builtin_amdgcn_readfirstlane(vstart[ne]);  // wave-uniform: loop bounds in SGPRs
   const int nt_r = (n_r + BN - 1) / BN;
   const int nt_c = (a < Cq) ? (Ck + BN - 1) / BN : 0;
   const int T = nt_r + nt_c;
@@ -513,7 +536,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
   const bf16_t* vc = p.vbar16 + (int64_t)bh * Ck * D;
 
   int cur = 0;  // segment cursor of threads 0..63 (virtual key position -> permuted row)
-  auto map_tile = [&](int t) {
+  auto map_tile = [&](int t) __attribute__((always_inline)) {
     if (tid < BN) {
       int phys;
       if (t < nt_r) {
@@ -533,62 +556,55 @@ attn_bf16_d128_kernel(AttnArgs p) {
   };
 
   // one wave-wide copy moves rows 4*inst .. 4*inst+3 of a tile; lane -> (row, LDS chunk slot).
-  // Copy i of this wave is instruction inst = wave + i*NW of the tile: its tile row, the
-  // swizzled 16-byte chunk it fetches and its LDS destination do not depend on the tile.
-  constexpr int CPW = INST_PER_TILE / NW;  // copies per tensor per wave per tile
-  const int cp_row = lane >> 4, cp_slot = lane & 15;
+  // Copy i of this wave is instruction inst = wave + i*CW of the tile: tile row cp_rr + 4*i*CW.
+  // CW is a multiple of 4, so the row's swizzle phases (row % 16, row % 4), and with them the
+  // 16-byte chunk a lane fetches, are the same for every i.
+  static_assert(CW % 4 == 0, "copy rows of one lane must share their swizzle phase");
+  constexpr int CPW = INST_PER_TILE / CW;  // copies per tensor per wave per tile
   const uint32_t lds_k0 = lds_address(Ks), lds_v0 = lds_address(Vs);
-  int cp_rr[CPW];
-  uint32_t cp_koff[CPW], cp_voff[CPW];
-#pragma unroll
-  for (int i = 0; i < CPW; ++i) {
-    cp_rr[i] = 4 * (wave + i * NW) + cp_row;
-    cp_koff[i] = (uint32_t)((cp_slot ^ (cp_rr[i] & 15)) << 4);
-    cp_voff[i] = (uint32_t)((cp_slot ^ ((cp_rr[i] & 3) << 2)) << 4);
-  }
+  const int cp_rr = 4 * (wave % CW) + (lane >> 4);
+  const uint32_t cp_koff = (uint32_t)(((lane & 15) ^ (cp_rr & 15)) << 4);
+  const uint32_t cp_voff = (uint32_t)(((lane & 15) ^ ((cp_rr & 3) << 2)) << 4);
   // permuted rows (of K/V or of the centroid tables) this lane copies for tile t
-  auto fetch_rows = [&](int t, int (&rows)[CPW]) {
-    const int32_t* rm = rowmap + (t % RS) * BN;
+  auto fetch_rows = [&](int t, int (&rows)[CPW]) __attribute__((always_inline)) {
+    const int32_t* rm = rowmap + (t % RS) * BN + cp_rr;
 #pragma unroll
-    for (int i = 0; i < CPW; ++i) rows[i] = rm[cp_rr[i]];
+    for (int i = 0; i < CPW; ++i) rows[i] = rm[4 * i * CW];
   };
-  auto issue_copies = [&](int t, const int (&rows)[CPW]) {
-    const bf16_t* kb = t < nt_r ? kh : kc;
-    const bf16_t* vb = t < nt_r ? vh : vc;
+  auto issue_copies = [&](int t) __attribute__((always_inline)) {
+    if (CW < NW && wave >= CW) return;
+    int rows[CPW];
+    fetch_rows(t, rows);
+    const void* kb = uniform_ptr(t < nt_r ? kh : kc);
+    const void* vb = uniform_ptr(t < nt_r ? vh : vc);
     const uint32_t kdst = lds_k0 + (t % NSTAGE) * TILE_BYTES + wave * 1024;
     const uint32_t vdst = lds_v0 + (t % NSTAGE) * TILE_BYTES + wave * 1024;
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
       const uint32_t rowoff = (uint32_t)rows[i] * (D * 2);
-      async_copy_16B(kb, rowoff + cp_koff[i], __builtin_amdgcn_readfirstlane(kdst + i * NW * 1024));
-      async_copy_16B(vb, rowoff + cp_voff[i], __builtin_amdgcn_readfirstlane(vdst + i * NW * 1024));
+      async_copy_16B(kb, rowoff + cp_koff, __builtin_amdgcn_readfirstlane(kdst + i * CW * 1024));
+      async_copy_16B(vb, rowoff + cp_voff, __builtin_amdgcn_readfirstlane(vdst + i * CW * 1024));
     }
-  };
-  auto issue_loads = [&](int t) {
-    int rows[CPW];
-    fetch_rows(t, rows);
-    issue_copies(t, rows);
   };
 
   // per-lane LDS byte offsets of the MFMA operands
   // K row li of a 32-row block, dims 16s + 8lh .. +7: chunk (2s + lh) ^ (li % 16)
-  int koff[KS];
-#pragma unroll
-  for (int s = 0; s < KS; ++s) koff[s] = li * 256 + (((2 * s + lh) ^ (li & 15)) << 4);
-  int voff[DB];  // transpose read: group = lane/16 -> (dim half, key half); r = lane%16
+  // (the swizzles are XORs of disjoint bit fields, so operand s / block db is the offset of
+  // operand 0 with s << 5 / db << 6 XORed in: one register each instead of a table)
+  const int koff0 = li * 256 + ((lh ^ (li & 15)) << 4);
+  auto koff = [&](int s) { return koff0 ^ (s << 5); };
+  int voff0;  // transpose read: group = lane/16 -> (dim half, key half); r = lane%16
   {
     const int r = lane & 15, g = lane >> 4, ddhalf = g & 1, khalf = g >> 1;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-      voff[db] = (4 * khalf + (r >> 2)) * 256 + ((4 * (db ^ (r >> 2)) + 2 * ddhalf + ((r & 3) >> 1)) << 4) + (r & 1) * 8;
+    voff0 = (4 * khalf + (r >> 2)) * 256 + ((4 * (r >> 2) + 2 * ddhalf + ((r & 3) >> 1)) << 4) + (r & 1) * 8;
   }
+  auto voff = [&](int db) { return voff0 ^ (db << 6); };
 
-  const int qrow = row0 + 32 * wave + li;
-  const bool qvalid = qrow < row_end;
   const bool wave_active = (row0 + 32 * wave) < row_end;
   bf16x8 bq[KS];
   {
-    const bf16_t* qr = static_cast<const bf16_t*>(p.qp) + ((int64_t)bh * p.Nq + (qvalid ? qrow : row_end - 1)) * D;
+    const int qrow = row0 + 32 * wave + li;
+    const bf16_t* qr = static_cast<const bf16_t*>(p.qp) + ((int64_t)bh * p.Nq + (qrow < row_end ? qrow : row_end - 1)) * D;
 #pragma unroll
     for (int s = 0; s < KS; ++s) bq[s] = as_bf16x8(*reinterpret_cast<const uint4*>(qr + 16 * s + 8 * lh));
   }
@@ -604,7 +620,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
   float m = -INFINITY, l = 0.f;
   const float c = p.scale * kLog2e;
 
-  auto rescale = [&](float m_new) {
+  auto rescale = [&](float m_new) __attribute__((always_inline)) {
     const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
     l *= alpha;
 #pragma unroll
@@ -614,42 +630,42 @@ attn_bf16_d128_kernel(AttnArgs p) {
     m = m_new;
   };
 
-  // One 64-key tile for this wave's 32 queries. BIASED = false: a full routed tile.
-  // BIASED = true: per-key additive bias (ragged routed tile: 0 / -inf; compensation tile:
-  // log2|k_b| or -inf).
-  auto compute_tile = [&](int t, auto biased_tag, auto&& after_scores) {
-    constexpr bool BIASED = decltype(biased_tag)::value;
+  // ---- S^T = K Q^T of tile t: 64 keys x 32 queries; register r of block kb is key
+  // 32kb + 8(r/4) + 4lh + r%4, query li. The scores of tile t+1 are computed at the end of
+  // pipeline step t (see below), so they live in registers across the tile barrier.
+  f32x16 sacc[2];
+  auto scores = [&](int t) __attribute__((always_inline)) {
     const unsigned char* Kb = Ks + (t % NSTAGE) * TILE_BYTES;
-    const unsigned char* Vb = Vs + (t % NSTAGE) * TILE_BYTES;
-    // ---- S^T = K Q^T : 64 keys x 32 queries; register r of block kb is key
-    // 32kb + 8(r/4) + 4lh + r%4, query li
-    f32x16 sacc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-    {
-      // the two 32-key blocks alternate so that consecutive MFMAs are independent; operand
-      // reads run four fragments ahead of the MFMAs that consume them
-      bf16x8 ak[2 * KS];
+    // the two 32-key blocks alternate so that consecutive MFMAs are independent; operand
+    // reads run four fragments ahead of the MFMAs that consume them
+    bf16x8 ak[2 * KS];
 #pragma unroll
-      for (int i = 0; i < 2 * KS; ++i)
-        ak[i] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (i & 1) * 32 * 256 + koff[i >> 1]));
+    for (int i = 0; i < 2 * KS; ++i)
+      ak[i] = as_bf16x8(*reinterpret_cast<const uint4*>(Kb + (i & 1) * 32 * 256 + koff(i >> 1)));
 #pragma unroll
-      for (int i = 0; i < 2 * KS; ++i)
-        sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[i], bq[i >> 1], sacc[i & 1], 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    for (int i = 0; i < 2 * KS; ++i)
+      sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[i], bq[i >> 1], sacc[i & 1], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-      for (int i = 0; i < 2 * KS - 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    for (int i = 0; i < 2 * KS - 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    after_scores();
-    // ---- online softmax in the base-2 domain; the running maximum m is refreshed lazily
-    // (only when a score exceeds it by more than 2^kLazyRescale), so O is rarely rescaled
-    uint32_t pk[2][8];
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  };
+
+  // ---- online softmax of tile t in the base-2 domain, from its scores in sacc to the packed
+  // bf16 probabilities pk; the running maximum m is refreshed lazily (only when a score
+  // exceeds it by more than 2^kLazyRescale), so O is rarely rescaled. BIASED = false: a full
+  // routed tile. BIASED = true: per-key additive bias (ragged routed tile: 0 / -inf;
+  // compensation tile: log2|k_b| or -inf).
+  uint32_t pk[2][8];
+  auto softmax = [&](int t, auto biased_tag) __attribute__((always_inline)) {
+    constexpr bool BIASED = decltype(biased_tag)::value;
     if constexpr (!BIASED) {
       // four independent max chains (a single chain of 16 dependent ops stalls the wave)
       float mxa = fmaxf(sacc[0][0], sacc[1][0]), mxb = fmaxf(sacc[0][1], sacc[1][1]);
@@ -716,14 +732,17 @@ attn_bf16_d128_kernel(AttnArgs p) {
         }
       l += (l0 + l1) + (l2 + l3);
     }
-    // ---- O^T += V^T P^T : k-step ks covers keys 16ks .. 16ks+15; the transpose reads of
-    // k-step ks+1 are issued before the MFMAs of k-step ks
+  };
+  // ---- O^T += V^T P^T of tile t: k-step ks covers keys 16ks .. 16ks+15; the transpose reads
+  // of k-step ks+1 are issued before the MFMAs of k-step ks
+  auto pv = [&](int t) __attribute__((always_inline)) {
+    const unsigned char* Vb = Vs + (t % NSTAGE) * TILE_BYTES;
     {
       bf16x8 av[4][DB];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) av[ks][db] = tr_pair(Vb, ks * 16 * 256 + voff[db]);
+        for (int db = 0; db < DB; ++db) av[ks][db] = tr_pair(Vb, ks * 16 * 256 + voff(db));
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const int kb = ks >> 1, u4 = (ks & 1) * 4;
@@ -743,41 +762,93 @@ attn_bf16_d128_kernel(AttnArgs p) {
     }
   };
 
-  // pipeline step around the compute of tile t: the rows of tile t+NSTAGE-1 are looked up
-  // first, its copies are issued once the score MFMAs are in flight (the copies have tiles
-  // of slack; the wave should not stall on the row lookup before feeding the matrix cores)
-  auto run_tile = [&](int t, auto biased_tag) {
+  // Pipeline step t (between two workgroup barriers). The three waves of a SIMD (wave / 4 =
+  // phase group) run the same three phases per step - scores, softmax, PV - but each group
+  // starts at a different one, so that while one wave is in its softmax (vector ALU) the other
+  // two have matrix work queued:
+  //   group 0:  S(t)   softmax(t)  PV(t)
+  //   group 1:  softmax(t)  PV(t)  S(t+1)            (prologue: S(0))
+  //   group 2:  PV(t)  S(t+1)  softmax(t+1)          (prologue: S(0), softmax(0))
+  // Step t therefore reads K(t), K(t+1) and V(t): both must have landed before it starts, and
+  // the buffers of tile t are free after its barrier; the copies of tile t+NSTAGE-1 are
+  // issued during step t.
+  static_assert(NW == 12, "three phase groups of four waves");
+  const int group = wave >> 2;
+  auto run_step = [&](int t, auto group_tag, auto biased_tag) __attribute__((always_inline)) {
+    constexpr int G = decltype(group_tag)::value;
     const bool more = t + NSTAGE - 1 < T;
-    int rows[CPW];
-    if (more) fetch_rows(t + NSTAGE - 1, rows);
-    if (wave_active) compute_tile(t, biased_tag, [&] { if (more) issue_copies(t + NSTAGE - 1, rows); });
-    else if (more) issue_copies(t + NSTAGE - 1, rows);
+    if (wave_active) {
+      if constexpr (G == 0) {
+        scores(t);
+        softmax(t, biased_tag);
+        pv(t);
+      } else if constexpr (G == 1) {
+        softmax(t, biased_tag);
+        pv(t);
+        __builtin_amdgcn_sched_barrier(0);  // keep the two MFMA pipelines in separate scheduling regions
+        // (unconditional, so the old and the new scores never have to be live together: the
+        // last step recomputes its own tile's scores, which nobody reads)
+        scores(t + 1 < T ? t + 1 : t);
+      } else {
+        pv(t);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < T) {
+          scores(t + 1);
+          softmax(t + 1, biased_tag);
+        } else {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) pk[kb][u] = 0u;
+        }
+      }
+    }
+    if (more) issue_copies(t + NSTAGE - 1);
     if (t + NSTAGE < T) map_tile(t + NSTAGE);
-    // this wave's copies of tile t+1 must have landed; younger tiles may stay in flight
-    if (more) SVGEAR_WAIT_VMCNT((NSTAGE - 2) * LOADS_PER_TILE);
+    // this wave's copies of tile t+2 must have landed (step t+1 reads K(t+2)); one younger
+    // tile may stay in flight
+    if (more) SVGEAR_WAIT_VMCNT((NSTAGE - 3) * LOADS_PER_TILE);
     else SVGEAR_WAIT_VMCNT(0);
     __syncthreads();
   };
 
-  // prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed
+  // prologue: tiles 0 .. NSTAGE-2 in flight, tiles 0 and 1 landed
 #pragma unroll
   for (int t = 0; t < NSTAGE; ++t)
     if (t < T) map_tile(t);
   __syncthreads();
 #pragma unroll
   for (int t = 0; t < NSTAGE - 1; ++t)
-    if (t < T) issue_loads(t);
-  if (T >= NSTAGE - 1) SVGEAR_WAIT_VMCNT((NSTAGE - 2) * LOADS_PER_TILE);
+    if (t < T) issue_copies(t);
+  if (T >= NSTAGE - 1) SVGEAR_WAIT_VMCNT((NSTAGE - 3) * LOADS_PER_TILE);
   else SVGEAR_WAIT_VMCNT(0);
   __syncthreads();
 
-  for (int t = 0; t < nt_full; ++t) run_tile(t, std::false_type{});
-  for (int t = nt_full; t < T; ++t) run_tile(t, std::true_type{});
+  // Every group runs T steps (T barriers). The bias tag belongs to the tile whose softmax the
+  // step contains: tile t for groups 0 and 1, tile t+1 for group 2.
+  if (group == 0) {
+    for (int t = 0; t < nt_full; ++t) run_step(t, std::integral_constant<int, 0>{}, std::false_type{});
+    for (int t = nt_full; t < T; ++t) run_step(t, std::integral_constant<int, 0>{}, std::true_type{});
+  } else if (group == 1) {
+    if (wave_active && T > 0) scores(0);
+    for (int t = 0; t < nt_full; ++t) run_step(t, std::integral_constant<int, 1>{}, std::false_type{});
+    for (int t = nt_full; t < T; ++t) run_step(t, std::integral_constant<int, 1>{}, std::true_type{});
+  } else {
+    if (wave_active && T > 0) {
+      scores(0);
+      if (nt_full > 0) softmax(0, std::false_type{});
+      else softmax(0, std::true_type{});
+    }
+    int t = 0;
+    for (; t + 1 < nt_full; ++t) run_step(t, std::integral_constant<int, 2>{}, std::false_type{});
+    for (; t < T; ++t) run_step(t, std::integral_constant<int, 2>{}, std::true_type{});
+  }
 
   // ---- epilogue: lane holds query li, dims 32db + 8g + 4lh + 0..3
   if (wave_active) {
     const float lt = l + swap32(l);
-    if (qvalid) {
+    const int qrow = row0 + 32 * wave + li;
+    if (qrow < row_end) {
       const float inv = lt > 0.f ? 1.0f / lt : 0.f;
       bf16_t* o = static_cast<bf16_t*>(p.op) + ((int64_t)bh * p.Nq + qrow) * D;
 #pragma unroll
@@ -794,12 +865,120 @@ attn_bf16_d128_kernel(AttnArgs p) {
   }
 }
 
+// ------------------------------------------------------------------------ work lists
+// Item = (head, query cluster); its tiles all run T = #routed key tiles + #centroid tiles
+// pipeline steps. Items are ranked by T, longest first (ties by index), and dealt to the 8
+// lists in boustrophedon order, which keeps the lists' totals close; inside a list the
+// longest come first, so a list's tail consists of its shortest tiles.
+__global__ void __launch_bounds__(256)
+plan_items_kernel(const int32_t* __restrict__ q_offsets, const int32_t* __restrict__ k_offsets,
+                  const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int Cq, int Ck, int BM,
+                  int32_t* __restrict__ item_T, int32_t* __restrict__ item_nt) {
+  const int bh = blockIdx.x, R = Cq + 1, Cc = Ck + 1;
+  const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
+  const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
+  const int32_t* rp = row_ptr + (int64_t)bh * (R + 1);
+  for (int a = threadIdx.x; a < R; a += 256) {
+    const int n = qo[a + 1] - qo[a];
+    const int32_t* ci = col_idx + (int64_t)bh * R * Cc + rp[a];
+    const int ne = rp[a + 1] - rp[a];
+    int64_t nr = 0;
+    for (int e = 0; e < ne; ++e) {
+      const int b = ci[e];
+      const int sz = ko[b + 1] - ko[b];
+      nr += sz > 0 ? sz : 0;
+    }
+    const int nt = n > 0 ? (n + BM - 1) / BM : 0;
+    item_nt[bh * R + a] = nt;
+    item_T[bh * R + a] = nt > 0 ? (int)((nr + BN - 1) / BN) + (a < Cq ? (Ck + BN - 1) / BN : 0) : 0;
+  }
+}
+
+__global__ void __launch_bounds__(256)
+plan_rank_kernel(const int32_t* __restrict__ item_T, int M, int32_t* __restrict__ by_rank) {
+  __shared__ uint64_t keys[256];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  // larger key = earlier: T descending, then index ascending
+  const uint64_t mine = i < M ? ((uint64_t)(uint32_t)item_T[i] << 32) | (uint32_t)(0x7fffffff - i) : 0;
+  int rank = 0;
+  for (int j0 = 0; j0 < M; j0 += 256) {
+    const int j = j0 + threadIdx.x;
+    keys[threadIdx.x] = j < M ? ((uint64_t)(uint32_t)item_T[j] << 32) | (uint32_t)(0x7fffffff - j) : 0;
+    __syncthreads();
+    const int lim = M - j0 < 256 ? M - j0 : 256;
+    for (int u = 0; u < lim; ++u) rank += keys[u] > mine;
+    __syncthreads();
+  }
+  if (i < M) by_rank[rank] = i;
+}
+
+// rank r -> (list, position): round r/8 deals one item to every list, odd rounds in reverse
+__device__ __forceinline__ int list_of_rank(int r) { return ((r >> 3) & 1) ? 7 - (r & 7) : (r & 7); }
+
+__global__ void __launch_bounds__(1024)
+plan_lists_kernel(const int32_t* __restrict__ q_offsets, const int32_t* __restrict__ item_nt,
+                  const int32_t* __restrict__ by_rank, int M, int Cq, int BM, int32_t* __restrict__ rank_off,
+                  int32_t* __restrict__ sched_bh, int32_t* __restrict__ sched_a, int32_t* __restrict__ sched_row0,
+                  int32_t* __restrict__ sched_x) {
+  __shared__ int32_t part[1024];
+  __shared__ int32_t total[8], first[8];
+  const int tid = threadIdx.x, R = Cq + 1;
+  const int rounds = (M + 7) / 8;
+  // exclusive offsets of every item inside its list (list xl = ranks 8k + pos(k, xl))
+  for (int xl = 0; xl < 8; ++xl) {
+    int carry = 0;
+    for (int k0 = 0; k0 < rounds; k0 += 1024) {
+      const int k = k0 + tid;
+      const int r = 8 * k + ((k & 1) ? 7 - xl : xl);
+      const int v = (k < rounds && r < M) ? item_nt[by_rank[r]] : 0;
+      part[tid] = v;
+      __syncthreads();
+      for (int o = 1; o < 1024; o <<= 1) {
+        const int t = tid >= o ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += t;
+        __syncthreads();
+      }
+      if (k < rounds && r < M) rank_off[r] = carry + part[tid] - v;
+      carry += part[1023];
+      __syncthreads();
+    }
+    if (tid == 0) total[xl] = carry;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int xl = 0; xl < 8; ++xl) {
+      first[xl] = run;
+      run += total[xl];
+    }
+  }
+  __syncthreads();
+  if (tid < 8) {
+    sched_x[tid] = first[tid];
+    sched_x[8 + tid] = total[tid];
+    sched_x[16 + tid] = 0;
+  }
+  for (int r = tid; r < M; r += 1024) {
+    const int i = by_rank[r], bh = i / R, a = i % R;
+    const int nt = item_nt[i];
+    const int base = first[list_of_rank(r)] + rank_off[r];
+    const int q0 = q_offsets[(int64_t)bh * (Cq + 2) + a];
+    for (int j = 0; j < nt; ++j) {
+      sched_bh[base + j] = bh;
+      sched_a[base + j] = a;
+      sched_row0[base + j] = q0 + j * BM;
+    }
+  }
+}
+
 }  // namespace
 
-// Tile shape of the d = 128 kernel: 8 waves x 32 query rows per workgroup (one workgroup per
-// CU, 2 waves per SIMD), 4 K/V tile buffers in flight.
-constexpr int kD128Waves = 8;
+// Tile shape of the d = 128 kernel: 12 waves x 32 query rows per workgroup (one workgroup per
+// CU, 3 waves per SIMD at 168 VGPRs), 4 K/V tile buffers.
+constexpr int kD128Waves = 12;
 constexpr int kD128Stages = 4;
+constexpr int kD128CopyWaves = 8;
 
 int attn_bf16_bm(int d) { return d == 128 ? 32 * kD128Waves : 32 * kBf16Waves; }
 
@@ -807,6 +986,40 @@ size_t attn_bf16_lds_bytes(int d, int Ck) {
   return d == 128 ? lds_bytes_d128(Ck, kD128Stages) : lds_bytes_generic(d, Ck);
 }
 
+size_t plan_d128_workspace(int BH, int Cq, int64_t Nq) {
+  const size_t M = (size_t)BH * (Cq + 1);
+  const size_t tiles = (size_t)BH * ((size_t)ceil_div(Nq, 32 * kD128Waves) + Cq + 1);
+  return 4 * align_up(M * 4, 256) + 3 * align_up(tiles * 4, 256) + align_up(24 * 4, 256);
+}
+
+int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
+  Workspace w(ws, ws_bytes);
+  const int M = a.BH * (a.Cq + 1), BM = 32 * kD128Waves;
+  const size_t tiles = (size_t)a.BH * ((size_t)ceil_div(a.Nq, BM) + a.Cq + 1);
+  int32_t* item_T = w.take<int32_t>(M);
+  int32_t* item_nt = w.take<int32_t>(M);
+  int32_t* by_rank = w.take<int32_t>(M);
+  int32_t* rank_off = w.take<int32_t>(M);
+  int32_t* sched_bh = w.take<int32_t>(tiles);
+  int32_t* sched_a = w.take<int32_t>(tiles);
+  int32_t* sched_row0 = w.take<int32_t>(tiles);
+  int32_t* sched_x = w.take<int32_t>(24);
+  if (!w.ok()) return SVGEAR_ERR_WORKSPACE;
+  plan_items_kernel<<<a.BH, 256, 0, s>>>(a.q_offsets, a.k_offsets, a.row_ptr, a.col_idx, a.Cq, a.Ck, BM, item_T, item_nt);
+  SVGEAR_LAUNCH_CHECK();
+  plan_rank_kernel<<<(unsigned)ceil_div(M, 256), 256, 0, s>>>(item_T, M, by_rank);
+  SVGEAR_LAUNCH_CHECK();
+  plan_lists_kernel<<<1, 1024, 0, s>>>(a.q_offsets, item_nt, by_rank, M, a.Cq, BM, rank_off, sched_bh, sched_a, sched_row0,
+                                      sched_x);
+  SVGEAR_LAUNCH_CHECK();
+  a.sched_bh = sched_bh;
+  a.sched_a = sched_a;
+  a.sched_row0 = sched_row0;
+  a.sched_x = sched_x;
+  return SVGEAR_OK;
+}
+
+// `total` workgroups: at least the number of tiles (one workgroup per tile; the rest exit).
 int launch_attn_bf16(const AttnArgs& a, int d, unsigned total, hipStream_t s) {
   const size_t lds = attn_bf16_lds_bytes(d, a.Ck);
   if (d == 64) {
@@ -815,7 +1028,8 @@ int launch_attn_bf16(const AttnArgs& a, int d, unsigned total, hipStream_t s) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     kern<<<total, 64 * kBf16Waves, lds, s>>>(a);
   } else {
-    auto kern = attn_bf16_d128_kernel<kD128Waves, kD128Stages>;
+    if (!a.sched_x) return SVGEAR_ERR_INVALID;
+    auto kern = attn_bf16_d128_kernel<kD128Waves, kD128Stages, kD128CopyWaves>;
     SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     kern<<<total, 64 * kD128Waves, lds, s>>>(a);
