@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # 1 GiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); only known for the default configuration of a workload.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {("wan", 0.25): 48.74e9}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {("wan", 0.25): 42.10e9}
 
 
 def parse():
@@ -365,7 +365,8 @@ def main():
         "achieved_density": density,
         "rel_l2_vs_oracle_sampled_rows": rel,
         "attention_stage": {"ms": attn_ms, "dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12},
-        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if wl.dtype == "bf16" else "attn_f32_kernel",
+        "roofline": {"bound": "mfma", "kernel": ("attn_bf16_d128_kernel" if wl.d == 128 else "attn_bf16_kernel") if wl.dtype == "bf16"
+                     else "attn_f32_kernel",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get((wl.name, wl.rho)) if wl.H == 40 else None,
