@@ -48,7 +48,7 @@ def _oracle_stage(wl, ref, Qp, Kp, Vp, mask):
     return orc.attention_comp(Qp, Kp, Vp, lq, lk, kb, vb, full_mask(mask, Cq, Ck), orc.scale_of(d))
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_f32_d128"])
+@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_manyk", "mini_f32_d128"])
 @pytest.mark.parametrize("mode", ["routed", "all", "none", "random"])
 def test_attention_stage_matches_oracle(name, mode):
     wl = get_workload(name)
@@ -107,7 +107,7 @@ def test_identical_keys_per_cluster_compensation_exact_on_gpu():
             assert rel_l2(to_np(op[b, h]), dense) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_f32_d128"])
+@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_manyk", "mini_f32_d128"])
 def test_end_to_end_chain_matches_oracle(name):
     wl = get_workload(name)
     Q, K, V = make_qkv(wl, dev())

@@ -26,7 +26,7 @@ def _run_full(name, iters):
     return wl, Q, K, V, cq0, ck0, O, r, budget
 
 
-@pytest.mark.parametrize("name", ["wan", "hunyuan"])
+@pytest.mark.parametrize("name", ["wan", "hunyuan", "wan_c300"])
 def test_full_size_layer_sampled_parity(name):
     iters = 2  # the clustering only has to be plausible here; lock-step parity is checked below
     wl, Q, K, V, cq0, ck0, O, r, budget = _run_full(name, iters)

@@ -52,7 +52,7 @@ def test_kmeans_lockstep_video_bf16_with_tail():
     _lockstep(Q, wl.Cq, 2, seed=wl.seed, tensor_id=0)
 
 
-@pytest.mark.parametrize("name", ["mini_d64", "mini_manyq", "mini_f32_d128"])
+@pytest.mark.parametrize("name", ["mini_d64", "mini_manyq", "mini_manyk", "mini_f32_d128"])
 def test_kmeans_lockstep_other_shapes(name):
     wl = get_workload(name)
     Q, K, V = make_qkv(wl, dev())

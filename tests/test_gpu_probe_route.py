@@ -37,7 +37,7 @@ def _check_scores(got, ref):
     assert not bad.any(), f"{bad.sum()} scores off, worst rel {np.max(np.abs(got - ref) / (np.abs(ref) + 1e-30))}"
 
 
-@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_f32_d128"])
+@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_manyk", "mini_f32_d128"])
 @pytest.mark.parametrize("plain", [False, True])
 def test_probe_scores_match_oracle(name, plain):
     wl, refs, qbar, kbar, vbar, Kp, Vp, qoff, koff = _stage_inputs(name)

@@ -56,6 +56,14 @@ WORKLOADS = {
     # HunyuanVideo-shaped layer: 33 x 45 x 80 video tokens + 256 text tokens, 24 heads.
     "hunyuan": Workload("hunyuan", 1, 24, 118800 + 256, 256, 128, 100, 500, 10, 0.25, "bf16", 256,
                         1.0, 0.3, (33, 45, 80), (4, 8, 8), 0),
+    # The same layers with the cluster counts the paper's experiments use (Experiment setup:
+    # Q_C / K_C = 300 / 1000 and 400 / 1000; Turbo variant 200 / 500 at a lower budget)
+    "wan_c300": Workload("wan_c300", 1, 40, 75600, 0, 128, 300, 1000, 10, 0.25, "bf16", 256, 1.0, 0.3,
+                         (21, 45, 80), (4, 8, 8), 0),
+    "hunyuan_c400": Workload("hunyuan_c400", 1, 24, 118800 + 256, 256, 128, 400, 1000, 10, 0.25, "bf16", 256,
+                             1.0, 0.3, (33, 45, 80), (4, 8, 8), 0),
+    "wan_turbo": Workload("wan_turbo", 1, 40, 75600, 0, 128, 200, 500, 10, 0.15, "bf16", 256, 1.0, 0.3,
+                          (21, 45, 80), (4, 8, 8), 0),
     # Scaled-down video-shaped cases used by the parity tests (oracle runs them in seconds).
     "mini_video": Workload("mini_video", 1, 2, 6 * 10 * 16, 0, 128, 12, 40, 4, 0.25, "bf16", 32,
                            1.0, 0.3, (6, 10, 16), (2, 4, 4), 3),
@@ -65,6 +73,10 @@ WORKLOADS = {
     "mini_manyq": Workload("mini_manyq", 1, 2, 900, 0, 128, 140, 20, 3, 0.25, "bf16", 24, 1.0, 0.3, None, None, 9),
     # fp32 with d = 128, batch of two
     "mini_f32_d128": Workload("mini_f32_d128", 2, 1, 700, 0, 128, 9, 33, 3, 0.25, "f32", 12, 1.5, 0.4, None, None, 11),
+    # many small key clusters (about 12 rows each, like K_C = 1000 on a full layer's scale
+    # relative to the 64-key tile) and more query clusters than key tiles
+    "mini_manyk": Workload("mini_manyk", 1, 2, 4 * 12 * 20, 0, 128, 30, 80, 3, 0.25, "bf16", 48, 1.0, 0.3,
+                           (4, 12, 20), (3, 4, 4), 13),
     "mini_video_tail": Workload("mini_video_tail", 1, 2, 5 * 9 * 14 + 37, 37, 128, 10, 30, 4,
                                 0.25, "bf16", 32, 1.0, 0.3, (5, 9, 14), (2, 4, 4), 5),
 }
