@@ -199,18 +199,39 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
     torch.cuda.synchronize()
     base = tm.stages_ms()
     dense_flops = 4.0 * wl.B * wl.H * float(wl.N) ** 2 * wl.d
+    from workloads import budget_pairs
+
+    def attend(budget, flags=0):
+        pr = sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], budget, scale, flags=flags)
+        return sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"], pr["mask_bits"],
+                                   pr["row_ptr"], pr["col_idx"], scale)[0]
+
+    def rel_l2(o, ref):  # per head, then averaged (fp32 on the GPU)
+        num = (o.float() - ref.float()).flatten(2).norm(dim=2)
+        return float((num / ref.float().flatten(2).norm(dim=2)).mean().item())
+
+    # quality axis on the synthetic data: distance of the layer's output from exact attention
+    # (this kernel with every block routed), for the value-aware probe (Eq. (7), default), the
+    # plain probe (Eq. (5)) and per-query-cluster budgets (the paper's implementation)
+    o_dense = attend(budget_pairs(1.0, wl.N, wl.N))
     rows = []
     for rho in [0.0, 0.05, 0.10, 0.15, 0.25, 0.50, 1.0]:
-        from workloads import budget_pairs
         budget = budget_pairs(rho, wl.N, wl.N)
         t_pr, pr = _time_ms(lambda: sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], budget,
                                                    scale))
-        t_at, _ = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
-                                                       pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale))
+        t_at, at = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
+                                                        pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale))
         dens = float(pr["routed_cost"].sum().item()) / (wl.B * wl.H * float(wl.N) ** 2)
-        rows.append({"rho": rho, "achieved_density": dens, "probe_route_ms": t_pr, "attention_ms": t_at,
-                     "layer_ms": base["kmeans"] + base["permute"] + base["unpermute"] + t_pr + t_at,
-                     "attention_routed_tflops": 4.0 * wl.d * float(pr["routed_cost"].sum().item()) / (t_at * 1e-3) / 1e12})
+        row = {"rho": rho, "achieved_density": dens, "probe_route_ms": t_pr, "attention_ms": t_at,
+               "layer_ms": base["kmeans"] + base["permute"] + base["unpermute"] + t_pr + t_at,
+               "attention_routed_tflops": 4.0 * wl.d * float(pr["routed_cost"].sum().item()) / (t_at * 1e-3) / 1e12,
+               "rel_l2_vs_all_routed": rel_l2(at[0], o_dense)}
+        del at
+        if 0.0 < rho < 1.0:
+            row["rel_l2_vs_all_routed_plain_probe"] = rel_l2(attend(budget, sv.PROBE_PLAIN), o_dense)
+            row["rel_l2_vs_all_routed_per_row_budget"] = rel_l2(attend(budget, sv.ROUTE_PER_ROW), o_dense)
+        rows.append(row)
+    del o_dense
     out = {"mode": "sweep", "workload": wl.name, "kmeans_ms": base["kmeans"], "permute_ms": base["permute"],
            "unpermute_ms": base["unpermute"], "sweep": rows}
     try:
