@@ -428,12 +428,15 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
 
 // Mean of the members of one cluster. A row is covered by LPR lanes of 16 bytes each; the
 // 256 threads form 256/LPR member slots. Slot s sums members s, s+SLOTS, ... in order;
-// slots are then added in slot order.
+// slots are then added in slot order. With gridDim.z = P > 1 the members are cut into P
+// contiguous parts (a fixed function of the cluster's size), part z writes its sum to
+// `partial` [BH][C][P][D] and means_finish_kernel adds the parts in order: a few very large
+// clusters no longer set the kernel's duration, and the result stays run-to-run identical.
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restrict__ perm, int64_t N,
              const int32_t* __restrict__ offsets, int C, float* __restrict__ cent,
-             int32_t* __restrict__ counts) {
+             int32_t* __restrict__ counts, float* __restrict__ partial) {
   constexpr int VEC = 16 / sizeof(T);  // elements per lane
   constexpr int LPR = D / VEC;         // lanes per row
   constexpr int SLOTS = 256 / LPR;
@@ -441,7 +444,11 @@ means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restri
   const int c = blockIdx.x, bh = blockIdx.y;
   const int slot = threadIdx.x / LPR, lane = threadIdx.x % LPR;
   const int32_t* off = offsets + (int64_t)bh * (C + 2);
-  const int start = off[c], end = off[c + 1];
+  const int c_start = off[c], c_end = off[c + 1];
+  const int P = gridDim.z, part = blockIdx.z;
+  const int part_len = (((c_end - c_start + P - 1) / P) + SLOTS - 1) / SLOTS * SLOTS;
+  const int start = c_start + part * part_len < c_end ? c_start + part * part_len : c_end;
+  const int end = start + part_len < c_end ? start + part_len : c_end;
   const int32_t* pm = perm + (int64_t)bh * N;
   const T* xb = x + head_base(st, bh, H) + lane * VEC;
   float acc[VEC];
@@ -473,14 +480,41 @@ means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restri
 #pragma unroll
   for (int k = 0; k < VEC; ++k) red[slot][lane * VEC + k] = acc[k];
   __syncthreads();
-  const int cnt = end - start;
-  if (threadIdx.x < D && cnt > 0) {
+  const int cnt = c_end - c_start;
+  if (threadIdx.x < D && (cnt > 0 || P > 1)) {
     float s = red[0][threadIdx.x];
 #pragma unroll
     for (int k = 1; k < SLOTS; ++k) s += red[k][threadIdx.x];
-    cent[((int64_t)bh * C + c) * D + threadIdx.x] = s / (float)cnt;
+    if (P == 1) cent[((int64_t)bh * C + c) * D + threadIdx.x] = s / (float)cnt;
+    else partial[(((int64_t)bh * C + c) * P + part) * D + threadIdx.x] = s;
   }
-  if (threadIdx.x == 0 && counts) counts[(int64_t)bh * C + c] = cnt;
+  if (P == 1 && threadIdx.x == 0 && counts) counts[(int64_t)bh * C + c] = cnt;
+}
+
+// Adds the P partial sums of every cluster in part order and divides by the member count; a
+// cluster without members keeps its centroid.
+__global__ void __launch_bounds__(256)
+means_finish_kernel(const float* __restrict__ partial, const int32_t* __restrict__ offsets, int C, int P, int D,
+                    float* __restrict__ cent, int32_t* __restrict__ counts) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (bh, c, dim)
+  const int bh = blockIdx.y;
+  if (i >= (int64_t)C * D) return;
+  const int c = (int)(i / D), dim = (int)(i % D);
+  const int32_t* off = offsets + (int64_t)bh * (C + 2);
+  const int cnt = off[c + 1] - off[c];
+  if (cnt > 0) {
+    const float* pp = partial + (((int64_t)bh * C + c) * P) * D + dim;
+    float s = pp[0];
+    for (int k = 1; k < P; ++k) s += pp[(int64_t)k * D];
+    cent[((int64_t)bh * C + c) * D + dim] = s / (float)cnt;
+  }
+  if (dim == 0 && counts) counts[(int64_t)bh * C + c] = cnt;
+}
+
+// Parts per cluster of the centroid update: about 128 members per part on average, at most 8.
+static inline int means_parts(int64_t n, int C) {
+  const int64_t p = (n / C + 64) / 128;
+  return (int)(p < 1 ? 1 : (p > 8 ? 8 : p));
 }
 
 template <typename T, int D>
@@ -498,6 +532,8 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   float* xnorm = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
   int32_t* amb_rows = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
   int32_t* amb_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
+  const int P = means_parts(nv, C);
+  float* partial = P > 1 ? ws.take<float>((size_t)BH * C * P * D) : nullptr;
   if (!ws.ok()) return SVGEAR_ERR_WORKSPACE;
   const size_t lds = 2 * (size_t)kCentChunk * D * 4 + 2 * kCentChunk * sizeof(float);
   auto assign = assign_mfma_kernel<T, D>;
@@ -513,6 +549,16 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   }
   const dim3 gp((unsigned)ceil_div((int64_t)Cpad * D, 256 * 4), BH);
   const dim3 ga((unsigned)ceil_div(nv, kAssignRows), BH);
+  auto update = [&](const T* src, float* dst, int32_t* cnt_out) -> int {
+    means_kernel<T, D><<<dim3(C, BH, P), 256, 0, s>>>(src, st, H, perm, nv, offsets, C, dst, cnt_out, partial);
+    SVGEAR_LAUNCH_CHECK();
+    if (P > 1) {
+      means_finish_kernel<<<dim3((unsigned)ceil_div((int64_t)C * D, 256), BH), 256, 0, s>>>(partial, offsets, C, P, D,
+                                                                                         dst, cnt_out);
+      SVGEAR_LAUNCH_CHECK();
+    }
+    return SVGEAR_OK;
+  };
   for (int it = 0; it < iters; ++it) {
     prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count);
     SVGEAR_LAUNCH_CHECK();
@@ -527,12 +573,12 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
     SVGEAR_LAUNCH_CHECK();
     int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s);
     if (rc != SVGEAR_OK) return rc;
-    means_kernel<T, D><<<dim3(C, BH), 256, 0, s>>>(x, st, H, perm, nv, offsets, C, cent, counts);
-    SVGEAR_LAUNCH_CHECK();
+    rc = update(x, cent, counts);
+    if (rc != SVGEAR_OK) return rc;
   }
   if (x2) {
-    means_kernel<T, D><<<dim3(C, BH), 256, 0, s>>>(x2, st, H, perm, nv, offsets, C, cent2, nullptr);
-    SVGEAR_LAUNCH_CHECK();
+    const int rc = update(x2, cent2, nullptr);
+    if (rc != SVGEAR_OK) return rc;
   }
   return SVGEAR_OK;
 }
@@ -549,7 +595,9 @@ extern "C" size_t svgear_kmeans_workspace(int B, int H, int64_t N, int d, int C)
   return align_up(BH * sort_chunks(N) * (C + 1) * 4, 256) + align_up(BH * N * 4, 256) +
          align_up(BH * (C + 2) * 4, 256) + align_up(BH * Cpad * 4, 256) + align_up(BH * Cpad * d * 4, 256) +
          // bf16 filter: hi/lo operand tables, row norms, ambiguous-row list and counter
-         align_up(BH * 2 * Cpad * d * 2, 256) + 2 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256);
+         align_up(BH * 2 * Cpad * d * 2, 256) + 2 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256) +
+         // partial sums of the split centroid update
+         (means_parts(N, C) > 1 ? align_up(BH * C * means_parts(N, C) * d * 4, 256) : 0);
 }
 
 extern "C" int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, int64_t N,
