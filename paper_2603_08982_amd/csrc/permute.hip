@@ -43,28 +43,65 @@ scan_kernel(int32_t* __restrict__ chunk_hist, int64_t N, int C, int nchunks,
   int32_t* offs = tot + (C + 1);
   const int bh = blockIdx.x;
   int32_t* hist = chunk_hist + (int64_t)bh * nchunks * (C + 1);
+  // label totals: loads only, eight in flight per thread
   for (int c = threadIdx.x; c <= C; c += kThreads) {
     int32_t run = 0;
-    for (int k = 0; k < nchunks; ++k) {
-      int32_t v = hist[(int64_t)k * (C + 1) + c];
-      hist[(int64_t)k * (C + 1) + c] = run;
-      run += v;
+    int k = 0;
+    for (; k + 8 <= nchunks; k += 8) {
+      int32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = hist[(int64_t)(k + u) * (C + 1) + c];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) run += v[u];
     }
+    for (; k < nchunks; ++k) run += hist[(int64_t)k * (C + 1) + c];
     tot[c] = run;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int32_t run = 0;
-    for (int c = 0; c <= C; ++c) {
+  // exclusive scan of the C+1 totals: each thread takes a contiguous run of labels
+  {
+    const int per = (C + 1 + kThreads - 1) / kThreads;
+    const int lo = threadIdx.x * per, hi = lo + per < C + 1 ? lo + per : C + 1;
+    int32_t sum = 0;
+    for (int c = lo; c < hi; ++c) sum += tot[c];
+    __shared__ int32_t part[kThreads];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int o = 1; o < kThreads; o <<= 1) {
+      const int32_t t = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+      __syncthreads();
+      part[threadIdx.x] += t;
+      __syncthreads();
+    }
+    int32_t run = part[threadIdx.x] - sum;
+    for (int c = lo; c < hi; ++c) {
       offs[c] = run;
       run += tot[c];
     }
   }
   __syncthreads();
+  // start of every (chunk, label) segment: offset of the label plus the label's count in the
+  // earlier chunks; eight chunks per round (loads first, then the stores)
   int32_t* o = offsets + (int64_t)bh * (C + 2);
   for (int c = threadIdx.x; c <= C; c += kThreads) {
-    o[c] = offs[c];
-    for (int k = 0; k < nchunks; ++k) hist[(int64_t)k * (C + 1) + c] += offs[c];
+    int32_t run = offs[c];
+    o[c] = run;
+    int k = 0;
+    for (; k + 8 <= nchunks; k += 8) {
+      int32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = hist[(int64_t)(k + u) * (C + 1) + c];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        hist[(int64_t)(k + u) * (C + 1) + c] = run;
+        run += v[u];
+      }
+    }
+    for (; k < nchunks; ++k) {
+      const int32_t v = hist[(int64_t)k * (C + 1) + c];
+      hist[(int64_t)k * (C + 1) + c] = run;
+      run += v;
+    }
   }
   if (threadIdx.x == 0) o[C + 1] = (int32_t)N;
 }
