@@ -43,11 +43,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 //  * amb_count (optional) is reset for the filter pass.
 __global__ void __launch_bounds__(256)
 prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, float* __restrict__ cperm,
-                      float* __restrict__ cn, bf16_t* __restrict__ chl, int32_t* __restrict__ amb_count) {
+                      float* __restrict__ cn, bf16_t* __restrict__ chl, int32_t* __restrict__ amb_count,
+                      int32_t* __restrict__ act_count) {
   const int bh = blockIdx.y;
   const float* cb = cent + (int64_t)bh * C * d;
   const int64_t n = (int64_t)Cpad * d;
   if (amb_count && blockIdx.x == 0 && threadIdx.x == 0) amb_count[bh] = 0;
+  if (act_count && blockIdx.x == 0 && threadIdx.x == 0) act_count[bh] = 0;
   if (chl) {
     const int ksn = d / 16;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
@@ -267,6 +269,39 @@ row_norm_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, flo
   xnorm[(int64_t)bh * nv + row] = sqrtf(acc) * 1.00002f;  // upper bound (the fp32 sum is within d 2^-24)
 }
 
+// How far every centroid moved since the previous call, |c - c_prev| rounded up, and
+// c_prev = c for the next one. One workgroup of D threads per centroid, fixed-order sum.
+template <int D>
+__global__ void __launch_bounds__(D)
+drift_kernel(const float* __restrict__ cent, int C, int Cpad, float* __restrict__ cent_prev,
+             float* __restrict__ drift) {
+  __shared__ float part[D / 64];
+  const int c = blockIdx.x, bh = blockIdx.y, k = threadIdx.x;
+  const int64_t i = ((int64_t)bh * C + c) * D + k;
+  const float v = cent[i], dv = v - cent_prev[i];
+  cent_prev[i] = v;
+  float s = dv * dv;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+  if ((k & 63) == 0) part[k >> 6] = s;
+  __syncthreads();
+  if (k == 0) {
+    float t = part[0];
+#pragma unroll
+    for (int w = 1; w < D / 64; ++w) t += part[w];
+    // upper bound (fp32 sum of D non-negative terms: relative error below D 2^-23)
+    drift[(int64_t)bh * Cpad + c] = sqrtf(t) * 1.0001f;
+  }
+}
+
+// Distance of a fixed-order fp32 score fma(-2, x.c, |c|^2) (both sums fmaf chains over d
+// terms) from the real number |c|^2 - 2 x.c, for |x| <= X and |c| <= Cm: d 2^-24 relative on
+// each chain plus the final rounding, with head room.
+template <int D>
+__device__ __forceinline__ float fixed_order_error(float X, float Cm) {
+  return (D + 2) * 5.9604644775390625e-08f * 1.001f * (Cm * Cm + 2.0f * X * Cm);
+}
+
 // Approximate scores s~(c) = fma(-2, x.hi_c + x.lo_c, |c|^2) on bf16 MFMAs, with the best and
 // second-best kept per row. With X = |x|_2, Cm = max_c |c|_2 and d the head dimension,
 //   |x.c(filter) - x.c(fixed order)| <= X Cm (2^-16 + (2d+1) 2^-23 + d 2^-24) =: X Cm kappa
@@ -281,7 +316,9 @@ template <int D>
 __global__ void __launch_bounds__(64 * kFilterWaves)
 assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, const bf16_t* __restrict__ chl,
                      const float* __restrict__ cn, const float* __restrict__ xnorm, int C, int Cpad,
-                     int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count) {
+                     int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
+                     const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
+                     float* __restrict__ ub, float* __restrict__ lb) {
   constexpr int KSN = D / 16;
   constexpr int CHUNK_BYTES = kCentChunk * D * 2 * 2;  // 64 centroids, hi and lo pieces
   constexpr int COPIES = CHUNK_BYTES / 1024 / kFilterCopyWaves;
@@ -290,6 +327,9 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   float* cns = reinterpret_cast<float*>(smem + 2 * CHUNK_BYTES);  // [Cpad] |c|^2 of every centroid
   float* red = cns + Cpad;                                        // [64 * kFilterWaves]
   const int bh = blockIdx.y;
+  // with a row list only the listed rows (row_count[bh] of them, in any order) are assigned
+  const int64_t n_rows = row_list ? row_count[bh] : nv;
+  if ((int64_t)blockIdx.x * kFilterRows >= n_rows) return;
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const float* cnb = cn + (int64_t)bh * Cpad;
@@ -312,12 +352,15 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
 
   // B operands: rows of two 32-row sets, dims 16s + 8 lh .. +7
   int64_t rows[2];
+  bool valid[2];
   bf16x8 bx[2][KSN];
 #pragma unroll
   for (int rs = 0; rs < 2; ++rs) {
-    rows[rs] = (int64_t)blockIdx.x * kFilterRows + kFilterRowsPerWave * wave + 32 * rs + li;
-    const int64_t lrow = rows[rs] < nv ? rows[rs] : nv - 1;
-    const bf16_t* xr = x + head_base(st, bh, H) + lrow * st.n;
+    const int64_t pos = (int64_t)blockIdx.x * kFilterRows + kFilterRowsPerWave * wave + 32 * rs + li;
+    valid[rs] = pos < n_rows;
+    const int64_t lpos = valid[rs] ? pos : n_rows - 1;
+    rows[rs] = row_list ? row_list[(int64_t)bh * nv + lpos] : lpos;
+    const bf16_t* xr = x + head_base(st, bh, H) + rows[rs] * st.n;
 #pragma unroll
     for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(*reinterpret_cast<const uint4*>(xr + 16 * s + 8 * lh));
   }
@@ -421,16 +464,146 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
     const float lo = fminf(best[rs], ob), hi = fmaxf(best[rs], ob);
     const float sec = fminf(hi, fminf(second[rs], os));
     const int a = (ob < best[rs] || (ob == best[rs] && oa < arg[rs])) ? oa : arg[rs];
-    if (lh == 0 && rows[rs] < nv) {
+    if (lh == 0 && valid[rs]) {
       const float X = xnorm[(int64_t)bh * nv + rows[rs]];
       const float B = 2.0f * X * Cm * kappa + 1.1920928955078125e-07f * (Cm * Cm + 2.0f * X * Cm);
       labels[(int64_t)bh * nv + rows[rs]] = a;
-      if (!(sec - lo > 2.0f * B * 1.0001f)) {  // also catches NaN / inf margins
-        const int slot = atomicAdd(&amb_count[bh], 1);
+      const bool ambiguous = !(sec - lo > 2.0f * B * 1.0001f);  // also catches NaN / inf margins
+      if (ambiguous) {
+        // one counter update for the ambiguous rows of the wave (the active lanes here)
+        const unsigned long long am = __ballot(1);
+        const int leader = __ffsll((long long)am) - 1;
+        int slot = 0;
+        if (lane == leader) slot = atomicAdd(&amb_count[bh], __popcll(am));
+        slot = __shfl(slot, leader) + __popcll(am & ((1ull << lane) - 1ull));
         amb_rows[(int64_t)bh * nv + slot] = (int32_t)rows[rs];
+      }
+      if (ub) {
+        // Distance bounds for the next iterations (see bounds_update_kernel): with F the
+        // distance of a filter score from the real |c|^2 - 2 x.c, the assigned centroid is at
+        // most sqrt(best + F + |x|^2) away and every other one at least
+        // sqrt(second - F + |x|^2). A row whose label the exact kernel decides gets no lower
+        // bound (it is assigned again next iteration).
+        const float F = B + fixed_order_error<D>(X, Cm);
+        const float x2_hi = X * X, x2_lo = X * X * 0.9999f;
+        const float u2 = lo + (ambiguous ? 2.0002f * B : 0.f) + F + x2_hi;
+        const float l2 = sec - F + x2_lo;
+        ub[(int64_t)bh * nv + rows[rs]] = sqrtf(fmaxf(u2, 0.f)) * 1.000001f;
+        lb[(int64_t)bh * nv + rows[rs]] = (ambiguous || !(l2 > 0.f)) ? 0.f : sqrtf(l2) * 0.999999f;
       }
     }
   }
+}
+
+constexpr int kBoundRows = 8;  // rows per thread of bounds_update_kernel
+
+// Per head: Cm^2 = max |c|^2, the largest and second largest centroid move, and whose the
+// largest is (stats[bh] = {Cm^2, d1, d2, a1 as float bits}); one workgroup per head.
+__global__ void __launch_bounds__(256)
+head_stats_kernel(const float* __restrict__ cn, const float* __restrict__ drift, int C, int Cpad,
+                  float* __restrict__ stats) {
+  __shared__ float s_cm2[4], s_d1[4], s_d2[4];
+  __shared__ int s_a1[4];
+  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float cm2 = 0.f, d1 = 0.f, d2 = 0.f;
+  int a1 = -1;
+  // (d1, a1, d2) of two disjoint sets of centroids -> of their union
+  auto merge = [&](float e1, int b1, float e2) {
+    if (e1 > d1) {
+      d2 = fmaxf(d1, e2);
+      d1 = e1;
+      a1 = b1;
+    } else {
+      d2 = fmaxf(d2, e1);
+    }
+  };
+  for (int c = tid; c < C; c += 256) {
+    cm2 = fmaxf(cm2, cn[(int64_t)bh * Cpad + c]);
+    merge(drift[(int64_t)bh * Cpad + c], c, 0.f);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    cm2 = fmaxf(cm2, __shfl_xor(cm2, o));
+    const float e1 = __shfl_xor(d1, o), e2 = __shfl_xor(d2, o);
+    const int b1 = __shfl_xor(a1, o);
+    merge(e1, b1, e2);
+  }
+  if (lane == 0) { s_cm2[wave] = cm2; s_d1[wave] = d1; s_d2[wave] = d2; s_a1[wave] = a1; }
+  __syncthreads();
+  if (tid == 0) {
+    cm2 = s_cm2[0]; d1 = s_d1[0]; d2 = s_d2[0]; a1 = s_a1[0];
+    for (int w = 1; w < 4; ++w) {
+      cm2 = fmaxf(cm2, s_cm2[w]);
+      merge(s_d1[w], s_a1[w], s_d2[w]);
+    }
+    stats[4 * bh + 0] = cm2;
+    stats[4 * bh + 1] = d1;
+    stats[4 * bh + 2] = d2;
+    stats[4 * bh + 3] = __int_as_float(a1);
+  }
+}
+
+// Which rows need a new assignment (Hamerly's bounds). ub[row] bounds the distance of the row
+// to its centroid from above, lb[row] its distance to every other centroid from below, both
+// for the centroids of the previous assignment. The centroids have since moved by at most
+// drift[c]; by the triangle inequality the row's centroid is now at most u = ub + drift[label]
+// away and every other at least l = lb - (largest drift among the others). If l^2 - u^2
+// exceeds twice the error E of a fixed-order fp32 score, the fixed-order argmin is the old
+// label, strictly, so the row is skipped and keeps its label with the widened bounds;
+// otherwise it is queued for the filter kernel. Skipping never changes a label, so the
+// result is the same as assigning every row in every iteration.
+template <int D>
+__global__ void __launch_bounds__(256)
+bounds_update_kernel(const int32_t* __restrict__ labels, const float* __restrict__ xnorm,
+                     const float* __restrict__ stats, const float* __restrict__ drift, int Cpad, int64_t nv,
+                     float* __restrict__ ub, float* __restrict__ lb, int32_t* __restrict__ act_rows,
+                     int32_t* __restrict__ act_count) {
+  const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float Cm = sqrtf(stats[4 * bh + 0]) * 1.00002f;
+  const float d1 = stats[4 * bh + 1], d2 = stats[4 * bh + 2];
+  const int a1 = __float_as_int(stats[4 * bh + 3]);
+
+  // kBoundRows rows per thread, 256 apart (a launch of one-row threads is bound by the rate at
+  // which workgroups start, not by memory)
+  unsigned qmask = 0;
+#pragma unroll
+  for (int j = 0; j < kBoundRows; ++j) {
+    const int64_t row = ((int64_t)blockIdx.x * kBoundRows + j) * 256 + tid;
+    if (row < nv) {
+      const int a = labels[(int64_t)bh * nv + row];
+      const float X = xnorm[(int64_t)bh * nv + row];
+      const float u = (ub[(int64_t)bh * nv + row] + drift[(int64_t)bh * Cpad + a]) * 1.000001f;
+      const float l = (lb[(int64_t)bh * nv + row] - (a == a1 ? d2 : d1)) * 0.999999f;
+      const float E = fixed_order_error<D>(X, Cm);
+      const bool keep = l > u && (l - u) * (l + u) > 2.002f * E;  // false for NaN
+      if (!keep) qmask |= 1u << j;
+      ub[(int64_t)bh * nv + row] = u;
+      lb[(int64_t)bh * nv + row] = l > 0.f ? l : 0.f;
+    }
+  }
+  // queue the rows of this workgroup with one counter update: exclusive scan of the per-thread
+  // counts (wave shuffles, then the four wave totals)
+  __shared__ int s_cnt[4], s_base;
+  const int cnt = __popc(qmask);
+  int incl = cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) s_cnt[wave] = incl;
+  __syncthreads();
+  if (tid == 0) {
+    const int total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+    s_base = total ? atomicAdd(&act_count[bh], total) : 0;
+  }
+  __syncthreads();
+  int pos = s_base + incl - cnt;
+  for (int w = 0; w < wave; ++w) pos += s_cnt[w];
+#pragma unroll
+  for (int j = 0; j < kBoundRows; ++j)
+    if (qmask & (1u << j))
+      act_rows[(int64_t)bh * nv + pos++] = (int32_t)(((int64_t)blockIdx.x * kBoundRows + j) * 256 + tid);
 }
 
 // Mean of the members of one cluster. A row is covered by LPR lanes of 16 bytes each; the
@@ -541,6 +714,14 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   int32_t* amb_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
   const int P = means_parts(nv, C);
   float* partial = P > 1 ? ws.take<float>((size_t)BH * C * P * D) : nullptr;
+  // row skipping between iterations (bf16 input): distance bounds, centroid moves, row queue
+  float* ub = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
+  float* lb = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
+  int32_t* act_rows = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
+  int32_t* act_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
+  float* cent_prev = kFilter ? ws.take<float>((size_t)BH * C * D) : nullptr;
+  float* drift = kFilter ? ws.take<float>((size_t)BH * Cpad) : nullptr;
+  float* stats = kFilter ? ws.take<float>((size_t)BH * 4) : nullptr;
   if (!ws.ok()) return SVGEAR_ERR_WORKSPACE;
   const size_t lds = 2 * (size_t)kCentChunk * D * 4 + 2 * kCentChunk * sizeof(float);
   auto assign = assign_mfma_kernel<T, D>;
@@ -567,11 +748,23 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
     return SVGEAR_OK;
   };
   for (int it = 0; it < iters; ++it) {
-    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count);
+    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count, act_count);
+    SVGEAR_LAUNCH_CHECK();
+    if constexpr (kFilter) drift_kernel<D><<<dim3(C, BH), D, 0, s>>>(cent, C, Cpad, cent_prev, drift);
     SVGEAR_LAUNCH_CHECK();
     if constexpr (kFilter) {
+      // first iteration: every row; later ones: only the rows whose bounds do not prove that
+      // their label stays
+      if (it > 0) {
+        head_stats_kernel<<<BH, 256, 0, s>>>(cn, drift, C, Cpad, stats);
+        SVGEAR_LAUNCH_CHECK();
+        bounds_update_kernel<D><<<dim3((unsigned)ceil_div(nv, 256 * kBoundRows), BH), 256, 0, s>>>(
+            labels, xnorm, stats, drift, Cpad, nv, ub, lb, act_rows, act_count);
+        SVGEAR_LAUNCH_CHECK();
+      }
       assign_filter_kernel<D><<<dim3((unsigned)ceil_div(nv, kFilterRows), BH), 64 * kFilterWaves, lds_f, s>>>(
-          reinterpret_cast<const bf16_t*>(x), st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count);
+          reinterpret_cast<const bf16_t*>(x), st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count,
+          it > 0 ? act_rows : nullptr, it > 0 ? act_count : nullptr, ub, lb);
       SVGEAR_LAUNCH_CHECK();
       assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, amb_rows, amb_count);
     } else {
@@ -604,7 +797,10 @@ extern "C" size_t svgear_kmeans_workspace(int B, int H, int64_t N, int d, int C)
          // bf16 filter: hi/lo operand tables, row norms, ambiguous-row list and counter
          align_up(BH * 2 * Cpad * d * 2, 256) + 2 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256) +
          // partial sums of the split centroid update
-         (means_parts(N, C) > 1 ? align_up(BH * C * means_parts(N, C) * d * 4, 256) : 0);
+         (means_parts(N, C) > 1 ? align_up(BH * C * means_parts(N, C) * d * 4, 256) : 0) +
+         // row skipping: two bounds and the row queue per row, counters, previous centroids, their moves
+         3 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256) + align_up(BH * C * d * 4, 256) +
+         align_up(BH * Cpad * 4, 256) + align_up(BH * 16, 256);
 }
 
 extern "C" int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, int64_t N,
