@@ -147,8 +147,11 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t n_rows = row_list ? row_count[bh] : nv;
-  if ((int64_t)blockIdx.x * kAssignRows >= n_rows) return;
-  const int64_t pos = (int64_t)blockIdx.x * kAssignRows + 32 * wave + li;
+  // block-stride loop over 256-row tiles: the refinement pass, whose row list is short and of
+  // unknown length at launch, runs on a quarter of the full grid (workgroups that find nothing
+  // to do still hold a slot until their row count arrives)
+  for (int64_t blk = blockIdx.x; blk * kAssignRows < n_rows; blk += gridDim.x) {
+  const int64_t pos = blk * kAssignRows + 32 * wave + li;
   const int64_t lpos = pos < n_rows ? pos : n_rows - 1;
   const int64_t row = row_list ? row_list[(int64_t)bh * nv + lpos] : lpos;
   float xb[D / 2];
@@ -230,6 +233,8 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const int oa = __shfl_xor(arg, 32);
   if (ob < best || (ob == best && oa < arg)) arg = oa;
   if (lh == 0 && pos < n_rows) labels[(int64_t)bh * nv + row] = arg;
+  __syncthreads();  // the LDS stages are refilled by the next tile
+  }
 }
 
 // ---- bf16 filter -----------------------------------------------------------------------
@@ -766,7 +771,8 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
           reinterpret_cast<const bf16_t*>(x), st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count,
           it > 0 ? act_rows : nullptr, it > 0 ? act_count : nullptr, ub, lb);
       SVGEAR_LAUNCH_CHECK();
-      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, amb_rows, amb_count);
+      assign<<<dim3((ga.x + 3) / 4, BH), 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, amb_rows,
+                                                                      amb_count);
     } else {
       assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, nullptr, nullptr);
     }
