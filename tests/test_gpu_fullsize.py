@@ -8,7 +8,7 @@ import torch
 
 import paper_2603_08982_amd as sv
 from oracle import svgear_oracle as orc
-from workloads import get_workload, make_qkv, budget_pairs
+from workloads import get_workload, make_qkv, budget_pairs, kmeans_init_indices
 from helpers import dev, to_np, init_centroids, bits_to_mask, full_mask, rel_l2
 
 pytestmark = pytest.mark.gpu
@@ -113,3 +113,30 @@ def test_full_size_kmeans_labels_bit_exact_wan():
         assert np.all(np.abs(to_np(ck[0, h]) - c_ref) <= 1e-5 * np.maximum(1.0, np.abs(c_ref)))
         ne = n_ref > 0
         assert np.all(np.abs(to_np(vbar[0, h])[ne] - v_ref[ne]) <= 1e-5 * np.maximum(1.0, np.abs(v_ref[ne])))
+
+
+@pytest.mark.parametrize("which", ["q", "k"])
+def test_full_size_kmeans_later_iterations_bit_exact_wan(which):
+    """Labels after 6 iterations at the Wan2.2 shape equal the oracle's fixed-order assignment
+    against the centroids after 5 iterations (the library is deterministic, so a 5-iteration
+    run reproduces them). From the second iteration on the library re-assigns only the rows
+    its distance bounds cannot settle; a wrongly skipped row would show up here."""
+    wl = get_workload("wan")
+    heads = [0, wl.H - 1]
+    Q, K, V = make_qkv(wl, dev(), heads=heads)
+    X, C, tensor_id = (Q, wl.Cq, 0) if which == "q" else (K, wl.Ck, 1)
+    c0 = torch.empty(1, len(heads), C, wl.d, device=dev())
+    for i, h in enumerate(heads):
+        idx = kmeans_init_indices(wl.seed, h, tensor_id, wl.N, C)
+        c0[0, i] = X[0, i][torch.from_numpy(idx).to(dev())].float()
+    c5 = c0.clone()
+    sv.kmeans(X, c5, 5)
+    c6 = c0.clone()
+    labels6, counts6, _ = sv.kmeans(X, c6, 6)
+    torch.cuda.synchronize()
+    for i in range(len(heads)):
+        l_ref = orc.kmeans_assign(to_np(X[0, i]), to_np(c5[0, i]))
+        assert np.array_equal(to_np(labels6[0, i]), l_ref)
+        c_ref, n_ref = orc.cluster_means(to_np(X[0, i]), l_ref, C, to_np(c5[0, i]))
+        assert np.array_equal(to_np(counts6[0, i]), n_ref)
+        assert np.all(np.abs(to_np(c6[0, i]) - c_ref) <= 1e-5 * np.maximum(1.0, np.abs(c_ref)))
