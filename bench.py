@@ -90,11 +90,13 @@ def run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget, timer=None):
     ck.copy_(ck0)
     scale = float(wl.d) ** -0.5
     if timer: timer.mark("start")
-    lab_q, qcnt, _ = sv.kmeans(Q, cq, wl.iters, wl.n_tail)
-    lab_k, kcnt, vbar = sv.kmeans(K, ck, wl.iters, wl.n_tail, x2=V)
+    # the Q call and the K/V call of a stage are independent: they run side by side on two
+    # streams and are joined before the stage's mark (as attention_layer does)
+    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = sv.run_pair(lambda: sv.kmeans(Q, cq, wl.iters, wl.n_tail),
+                                                        lambda: sv.kmeans(K, ck, wl.iters, wl.n_tail, x2=V))
     if timer: timer.mark("kmeans")
-    perm_q, qoff, (Qp,) = sv.permute(lab_q, wl.Cq, [Q], wl.n_tail)
-    perm_k, koff, (Kp, Vp) = sv.permute(lab_k, wl.Ck, [K, V], wl.n_tail)
+    (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = sv.run_pair(
+        lambda: sv.permute(lab_q, wl.Cq, [Q], wl.n_tail), lambda: sv.permute(lab_k, wl.Ck, [K, V], wl.n_tail))
     if timer: timer.mark("permute")
     r = sv.probe_route(cq, ck, vbar, Kp, Vp, qoff, koff, budget, scale)
     if timer: timer.mark("probe_route")

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     sparse_attn_comp,
     unpermute,
     attention_layer,
+    run_pair,
     EXPORTED_SYMBOLS,
     PROBE_PLAIN,
     ROUTE_PER_ROW,

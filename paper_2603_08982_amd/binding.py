@@ -234,9 +234,43 @@ def unpermute(op: torch.Tensor, perm: torch.Tensor, out: Optional[torch.Tensor] 
     return out
 
 
+_SIDE_STREAMS = {}
+
+
+def run_pair(fn_side, fn_main):
+    """Runs two independent library calls concurrently: fn_side on a second stream of the
+    same device (default priority), fn_main on the current stream, and joins them. The
+    k-means and permutation calls of Q and of K/V do not depend on each other and their small
+    kernels leave CUs idle, so running the two side by side shortens the layer (measured
+    14.2 -> 12.9 ms for both k-means and permutations at the Wan shape). Tensors fn_side
+    returns are handed over to the current stream. Returns (fn_side(), fn_main())."""
+    main = torch.cuda.current_stream()
+    key = main.device_index
+    side = _SIDE_STREAMS.get(key)
+    if side is None:
+        side = _SIDE_STREAMS[key] = torch.cuda.Stream(device=main.device)
+    side.wait_stream(main)
+    with torch.cuda.stream(side):
+        a = fn_side()
+    b = fn_main()
+    main.wait_stream(side)
+
+    def hand_over(x):
+        if isinstance(x, torch.Tensor):
+            x.record_stream(main)
+        elif isinstance(x, (tuple, list)):
+            for y in x:
+                hand_over(y)
+
+    hand_over(a)
+    return a, b
+
+
 def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tail: int = 0, flags: int = 0,
-                    scale: Optional[float] = None):
-    """One pass of the whole hot path over a batch of heads: the five library calls in order.
+                    scale: Optional[float] = None, overlap: bool = True):
+    """One pass of the whole hot path over a batch of heads: the five library calls in order
+    (with overlap=True the Q and the K/V call of k-means, and then of the permutation, run
+    side by side on two streams).
 
     init_q [B,H,Cq,d], init_k [B,H,Ck,d] fp32 are the starting centroids (updated in place,
     so a caller can carry them to the next denoising step). Returns (O, intermediates)."""
@@ -244,10 +278,11 @@ def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tai
     if scale is None:
         scale = float(d) ** -0.5
     Cq, Ck = init_q.shape[2], init_k.shape[2]
-    lab_q, qcnt, _ = kmeans(Q, init_q, iters, n_tail)
-    lab_k, kcnt, vbar = kmeans(K, init_k, iters, n_tail, x2=V)
-    perm_q, qoff, (Qp,) = permute(lab_q, Cq, [Q], n_tail)
-    perm_k, koff, (Kp, Vp) = permute(lab_k, Ck, [K, V], n_tail)
+    pair = run_pair if overlap else (lambda f, g: (f(), g()))
+    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = pair(lambda: kmeans(Q, init_q, iters, n_tail),
+                                                 lambda: kmeans(K, init_k, iters, n_tail, x2=V))
+    (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = pair(lambda: permute(lab_q, Cq, [Q], n_tail),
+                                                           lambda: permute(lab_k, Ck, [K, V], n_tail))
     r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags)
     Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
     O = unpermute(Op, perm_q)
