@@ -44,7 +44,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 __global__ void __launch_bounds__(256)
 prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, float* __restrict__ cperm,
                       float* __restrict__ cn, bf16_t* __restrict__ chl, int32_t* __restrict__ amb_count,
-                      int32_t* __restrict__ act_count) {
+                      int32_t* __restrict__ act_count, int32_t* __restrict__ dirty) {
   const int bh = blockIdx.y;
   const float* cb = cent + (int64_t)bh * C * d;
   const int64_t n = (int64_t)Cpad * d;
@@ -73,6 +73,7 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
     cperm[(int64_t)bh * n + i] = c < C ? cb[(int64_t)c * d + k] : 0.f;
   }
   for (int c = blockIdx.x * 256 + threadIdx.x; c < Cpad; c += gridDim.x * 256) {
+    if (dirty) dirty[(int64_t)bh * Cpad + c] = 0;  // no cluster has gained or lost a member yet
     float acc = INFINITY;
     if (c < C) {
       acc = 0.f;
@@ -136,7 +137,8 @@ template <typename T, int D>
 __global__ void __launch_bounds__(64 * kAssignWaves)
 assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const float* __restrict__ cperm,
                    const float* __restrict__ cn, int Cpad, int32_t* __restrict__ labels,
-                   const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count) {
+                   const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
+                   int32_t* __restrict__ dirty) {
   constexpr int QG = D / 8;                        // 16-byte operand groups per block
   constexpr int CHUNK_BYTES = kCentChunk * D * 4;  // one LDS stage of centroids
   constexpr int COPIES = CHUNK_BYTES / 1024 / kAssignWaves;
@@ -232,7 +234,16 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const float ob = __shfl_xor(best, 32);
   const int oa = __shfl_xor(arg, 32);
   if (ob < best || (ob == best && oa < arg)) arg = oa;
-  if (lh == 0 && pos < n_rows) labels[(int64_t)bh * nv + row] = arg;
+  if (lh == 0 && pos < n_rows) {
+    if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
+      const int cur = labels[(int64_t)bh * nv + row];
+      if (cur != arg) {
+        dirty[(int64_t)bh * Cpad + cur] = 1;
+        dirty[(int64_t)bh * Cpad + arg] = 1;
+      }
+    }
+    labels[(int64_t)bh * nv + row] = arg;
+  }
   __syncthreads();  // the LDS stages are refilled by the next tile
   }
 }
@@ -323,7 +334,7 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
                      const float* __restrict__ cn, const float* __restrict__ xnorm, int C, int Cpad,
                      int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
                      const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
-                     float* __restrict__ ub, float* __restrict__ lb) {
+                     float* __restrict__ ub, float* __restrict__ lb, int32_t* __restrict__ dirty) {
   constexpr int KSN = D / 16;
   constexpr int CHUNK_BYTES = kCentChunk * D * 2 * 2;  // 64 centroids, hi and lo pieces
   constexpr int COPIES = CHUNK_BYTES / 1024 / kFilterCopyWaves;
@@ -472,6 +483,13 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
     if (lh == 0 && valid[rs]) {
       const float X = xnorm[(int64_t)bh * nv + rows[rs]];
       const float B = 2.0f * X * Cm * kappa + 1.1920928955078125e-07f * (Cm * Cm + 2.0f * X * Cm);
+      if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
+        const int cur = labels[(int64_t)bh * nv + rows[rs]];
+        if (cur != a) {
+          dirty[(int64_t)bh * Cpad + cur] = 1;
+          dirty[(int64_t)bh * Cpad + a] = 1;
+        }
+      }
       labels[(int64_t)bh * nv + rows[rs]] = a;
       const bool ambiguous = !(sec - lo > 2.0f * B * 1.0001f);  // also catches NaN / inf margins
       if (ambiguous) {
@@ -621,12 +639,15 @@ template <typename T, int D>
 __global__ void __launch_bounds__(256)
 means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restrict__ perm, int64_t N,
              const int32_t* __restrict__ offsets, int C, float* __restrict__ cent,
-             int32_t* __restrict__ counts, float* __restrict__ partial) {
+             int32_t* __restrict__ counts, float* __restrict__ partial, const int32_t* __restrict__ dirty,
+             int Cpad) {
   constexpr int VEC = 16 / sizeof(T);  // elements per lane
   constexpr int LPR = D / VEC;         // lanes per row
   constexpr int SLOTS = 256 / LPR;
   __shared__ float red[SLOTS][D];
   const int c = blockIdx.x, bh = blockIdx.y;
+  // a cluster whose membership did not change keeps its centroid and count (same sum)
+  if (dirty && !dirty[(int64_t)bh * Cpad + c]) return;
   const int slot = threadIdx.x / LPR, lane = threadIdx.x % LPR;
   const int32_t* off = offsets + (int64_t)bh * (C + 2);
   const int c_start = off[c], c_end = off[c + 1];
@@ -680,11 +701,13 @@ means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restri
 // cluster without members keeps its centroid.
 __global__ void __launch_bounds__(256)
 means_finish_kernel(const float* __restrict__ partial, const int32_t* __restrict__ offsets, int C, int P, int D,
-                    float* __restrict__ cent, int32_t* __restrict__ counts) {
+                    float* __restrict__ cent, int32_t* __restrict__ counts, const int32_t* __restrict__ dirty,
+                    int Cpad) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (bh, c, dim)
   const int bh = blockIdx.y;
   if (i >= (int64_t)C * D) return;
   const int c = (int)(i / D), dim = (int)(i % D);
+  if (dirty && !dirty[(int64_t)bh * Cpad + c]) return;
   const int32_t* off = offsets + (int64_t)bh * (C + 2);
   const int cnt = off[c + 1] - off[c];
   if (cnt > 0) {
@@ -727,6 +750,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   float* cent_prev = kFilter ? ws.take<float>((size_t)BH * C * D) : nullptr;
   float* drift = kFilter ? ws.take<float>((size_t)BH * Cpad) : nullptr;
   float* stats = kFilter ? ws.take<float>((size_t)BH * 4) : nullptr;
+  int32_t* dirty = kFilter ? ws.take<int32_t>((size_t)BH * Cpad) : nullptr;
   if (!ws.ok()) return SVGEAR_ERR_WORKSPACE;
   const size_t lds = 2 * (size_t)kCentChunk * D * 4 + 2 * kCentChunk * sizeof(float);
   auto assign = assign_mfma_kernel<T, D>;
@@ -742,18 +766,21 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   }
   const dim3 gp((unsigned)ceil_div((int64_t)Cpad * D, 256 * 4), BH);
   const dim3 ga((unsigned)ceil_div(nv, kAssignRows), BH);
-  auto update = [&](const T* src, float* dst, int32_t* cnt_out) -> int {
-    means_kernel<T, D><<<dim3(C, BH, P), 256, 0, s>>>(src, st, H, perm, nv, offsets, C, dst, cnt_out, partial);
+  // only_changed: clusters that neither gained nor lost a member in this iteration keep their
+  // centroid (flags set by the assignment kernels; null = every cluster)
+  auto update = [&](const T* src, float* dst, int32_t* cnt_out, const int32_t* only_changed) -> int {
+    means_kernel<T, D><<<dim3(C, BH, P), 256, 0, s>>>(src, st, H, perm, nv, offsets, C, dst, cnt_out, partial,
+                                                      only_changed, Cpad);
     SVGEAR_LAUNCH_CHECK();
     if (P > 1) {
-      means_finish_kernel<<<dim3((unsigned)ceil_div((int64_t)C * D, 256), BH), 256, 0, s>>>(partial, offsets, C, P, D,
-                                                                                         dst, cnt_out);
+      means_finish_kernel<<<dim3((unsigned)ceil_div((int64_t)C * D, 256), BH), 256, 0, s>>>(
+          partial, offsets, C, P, D, dst, cnt_out, only_changed, Cpad);
       SVGEAR_LAUNCH_CHECK();
     }
     return SVGEAR_OK;
   };
   for (int it = 0; it < iters; ++it) {
-    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count, act_count);
+    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count, act_count, dirty);
     SVGEAR_LAUNCH_CHECK();
     if constexpr (kFilter) drift_kernel<D><<<dim3(C, BH), D, 0, s>>>(cent, C, Cpad, cent_prev, drift);
     SVGEAR_LAUNCH_CHECK();
@@ -769,21 +796,21 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
       }
       assign_filter_kernel<D><<<dim3((unsigned)ceil_div(nv, kFilterRows), BH), 64 * kFilterWaves, lds_f, s>>>(
           reinterpret_cast<const bf16_t*>(x), st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count,
-          it > 0 ? act_rows : nullptr, it > 0 ? act_count : nullptr, ub, lb);
+          it > 0 ? act_rows : nullptr, it > 0 ? act_count : nullptr, ub, lb, it > 0 ? dirty : nullptr);
       SVGEAR_LAUNCH_CHECK();
       assign<<<dim3((ga.x + 3) / 4, BH), 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, amb_rows,
-                                                                      amb_count);
+                                                                      amb_count, it > 0 ? dirty : nullptr);
     } else {
-      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, nullptr, nullptr);
+      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, nullptr, nullptr, nullptr);
     }
     SVGEAR_LAUNCH_CHECK();
     int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s);
     if (rc != SVGEAR_OK) return rc;
-    rc = update(x, cent, counts);
+    rc = update(x, cent, counts, (kFilter && it > 0) ? dirty : nullptr);
     if (rc != SVGEAR_OK) return rc;
   }
   if (x2) {
-    const int rc = update(x2, cent2, nullptr);
+    const int rc = update(x2, cent2, nullptr, nullptr);
     if (rc != SVGEAR_OK) return rc;
   }
   return SVGEAR_OK;
@@ -806,7 +833,9 @@ extern "C" size_t svgear_kmeans_workspace(int B, int H, int64_t N, int d, int C)
          (means_parts(N, C) > 1 ? align_up(BH * C * means_parts(N, C) * d * 4, 256) : 0) +
          // row skipping: two bounds and the row queue per row, counters, previous centroids, their moves
          3 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256) + align_up(BH * C * d * 4, 256) +
-         align_up(BH * Cpad * 4, 256) + align_up(BH * 16, 256);
+         align_up(BH * Cpad * 4, 256) + align_up(BH * 16, 256) +
+         // membership-changed flag per cluster
+         align_up(BH * Cpad * 4, 256);
 }
 
 extern "C" int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, int64_t N,
