@@ -230,6 +230,11 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
                "rel_l2_vs_all_routed": rel_l2(at[0], o_dense)}
         del at
         if 0.0 < rho < 1.0:
+            # Algorithm 2's two-stage form (routed pass, compensation pass, merge) on the same mask
+            t_2s, _ = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"],
+                                                           r["koff"], pr["mask_bits"], pr["row_ptr"], pr["col_idx"],
+                                                           scale, two_stage=True))
+            row["attention_two_stage_ms"] = t_2s
             row["rel_l2_vs_all_routed_plain_probe"] = rel_l2(attend(budget, sv.PROBE_PLAIN), o_dense)
             row["rel_l2_vs_all_routed_per_row_budget"] = rel_l2(attend(budget, sv.ROUTE_PER_ROW), o_dense)
         rows.append(row)

@@ -165,6 +165,23 @@ int svgear_sparse_attn_comp(const void* qp, const void* kp, const void* vp, svge
                             float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * The same result in the two-stage form of Algorithm 2, for comparison with the fused kernel:
+ * (1) block-sparse exact attention over the routed blocks alone -> (O_r, LSE_r); (2) the
+ * pseudo-keys of the skipped clusters alone -> (O_c, LSE_c); (3) merge:
+ * op = (e^{LSE_r} O_r + e^{LSE_c} O_c) / (e^{LSE_r} + e^{LSE_c}), lse = log of that
+ * denominator. Arguments as svgear_sparse_attn_comp; only dt = SVGEAR_BF16 with d = 128
+ * (SVGEAR_ERR_UNSUPPORTED otherwise). The workspace also holds the two partial results.
+ */
+size_t svgear_sparse_attn_two_stage_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
+                                              int Ck);
+int svgear_sparse_attn_two_stage(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
+                                 const float* kbar, const float* vbar, const int32_t* q_offsets,
+                                 const int32_t* k_offsets, const uint32_t* mask_bits,
+                                 const int32_t* row_ptr, const int32_t* col_idx, int B, int H,
+                                 int64_t Nq, int64_t Nk, int d, int Cq, int Ck, float scale,
+                                 void* op, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * unpermute: o[bh][perm[p]][:] = op[bh][p][:]  (inverse of the layout of "Structured
  * Redundancy").  op [BH,N,d] dense, perm [BH,N], o [B,H,N,d] with strides ostride.
  */

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "svgear_permute_workspace", "svgear_permute",
     "svgear_probe_route_workspace", "svgear_probe_route",
     "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp",
+    "svgear_sparse_attn_two_stage_workspace", "svgear_sparse_attn_two_stage",
     "svgear_unpermute",
 ]
 
@@ -74,6 +75,10 @@ def load_library():
     lib.svgear_sparse_attn_comp.restype = _i
     lib.svgear_sparse_attn_comp.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i64,
                                             _i64, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]
+    lib.svgear_sparse_attn_two_stage_workspace.restype = _sz
+    lib.svgear_sparse_attn_two_stage_workspace.argtypes = lib.svgear_sparse_attn_comp_workspace.argtypes
+    lib.svgear_sparse_attn_two_stage.restype = _i
+    lib.svgear_sparse_attn_two_stage.argtypes = lib.svgear_sparse_attn_comp.argtypes
     lib.svgear_unpermute.restype = _i
     lib.svgear_unpermute.argtypes = [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _c.POINTER(_c.c_int64), _vp]
     _LIB = lib
@@ -199,10 +204,13 @@ def probe_route(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, budget_cost: int
 
 
 def sparse_attn_comp(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, scale: float,
-                     want_lse: bool = False, ws: Optional[torch.Tensor] = None):
-    """svgear_sparse_attn_comp. Returns (op [B,H,Nq,d], lse or None)."""
+                     want_lse: bool = False, ws: Optional[torch.Tensor] = None, two_stage: bool = False):
+    """svgear_sparse_attn_comp (two_stage=True: svgear_sparse_attn_two_stage, the same result
+    through separate routed / compensation passes and a merge). Returns (op [B,H,Nq,d], lse or None)."""
     _need_gpu(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx)
     lib = load_library()
+    ws_fn = lib.svgear_sparse_attn_two_stage_workspace if two_stage else lib.svgear_sparse_attn_comp_workspace
+    fn = lib.svgear_sparse_attn_two_stage if two_stage else lib.svgear_sparse_attn_comp
     B, H, Nq, d = qp.shape
     Nk = kp.shape[2]
     Cq = q_offsets.shape[2] - 2
@@ -212,12 +220,11 @@ def sparse_attn_comp(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, ro
     op = torch.empty_like(qp)
     lse = torch.empty(B, H, Nq, dtype=torch.float32, device=qp.device) if want_lse else None
     if ws is None:
-        ws = _ws(lib.svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck), qp.device)
-    rc = lib.svgear_sparse_attn_comp(_ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar),
-                                     _ptr(q_offsets), _ptr(k_offsets), _ptr(mask_bits), _ptr(row_ptr),
-                                     _ptr(col_idx), B, H, Nq, Nk, d, Cq, Ck, float(scale), _ptr(op), _ptr(lse),
-                                     _ptr(ws), ws.numel(), _stream())
-    _check(rc, "svgear_sparse_attn_comp")
+        ws = _ws(ws_fn(B, H, Nq, Nk, d, Cq, Ck), qp.device)
+    rc = fn(_ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar), _ptr(q_offsets), _ptr(k_offsets),
+            _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), B, H, Nq, Nk, d, Cq, Ck, float(scale), _ptr(op), _ptr(lse),
+            _ptr(ws), ws.numel(), _stream())
+    _check(rc, "svgear_sparse_attn_two_stage" if two_stage else "svgear_sparse_attn_comp")
     return op, lse
 
 

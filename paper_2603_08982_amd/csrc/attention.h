@@ -35,6 +35,7 @@ struct AttnArgs {
   float scale;
   void* op;
   float* lse;
+  int part;  // 0: routed blocks and compensation (fused); 1: routed blocks only; 2: compensation only
 };
 
 __device__ __forceinline__ bool mask_bit(const uint32_t* mrow, int b) { return (mrow[b >> 5] >> (b & 31)) & 1u; }
@@ -53,5 +54,9 @@ int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s);
 size_t attn_bf16_lds_bytes(int d, int Ck);
 // Launches the bf16 MFMA kernel over `total` (multiple of 8) workgroups.
 int launch_attn_bf16(const AttnArgs& a, int d, unsigned total, hipStream_t s);
+
+// out = merge of (o1, lse1) and (o2, lse2), partial softmax results over disjoint key sets.
+int launch_merge(const bf16_t* o1, const float* lse1, const bf16_t* o2, const float* lse2, int64_t rows, int d,
+                 bf16_t* out, float* lse, hipStream_t s);
 
 }  // namespace svgear

@@ -212,12 +212,10 @@ extern "C" size_t svgear_sparse_attn_comp_workspace(int B, int H, int64_t Nq, in
          plan_d128_workspace((int)BH, Cq, Nq);
 }
 
-extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
-                                       const float* kbar, const float* vbar, const int32_t* q_offsets,
-                                       const int32_t* k_offsets, const uint32_t* mask_bits, const int32_t* row_ptr,
-                                       const int32_t* col_idx, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
-                                       int Ck, float scale, void* op, float* lse, void* ws, size_t ws_bytes,
-                                       void* stream) {
+static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype dt, const float* kbar,
+                    const float* vbar, const int32_t* q_offsets, const int32_t* k_offsets, const uint32_t* mask_bits,
+                    const int32_t* row_ptr, const int32_t* col_idx, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
+                    int Ck, float scale, void* op, float* lse, void* ws, size_t ws_bytes, void* stream, int part) {
   if (!qp || !kp || !vp || !kbar || !vbar || !q_offsets || !k_offsets || !mask_bits || !row_ptr || !col_idx || !op ||
       B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || Cq <= 0 || Ck <= 0 || Cq > 8192 || Ck > 8192 ||
       Nq > INT32_MAX / 2 || Nk > INT32_MAX / 2 || (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) ||
@@ -229,6 +227,7 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
   if (!ws || ws_bytes < svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck)) return SVGEAR_ERR_WORKSPACE;
   const int BH = B * H;
   if ((int64_t)BH * ((int64_t)ceil_div(Nq, 64) + Cq + 1) > INT32_MAX / 2) return SVGEAR_ERR_UNSUPPORTED;
+  if (part != 0 && !(dt == SVGEAR_BF16 && d == 128)) return SVGEAR_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   Workspace w(ws, ws_bytes);
   const int BM = attn_bm(dt, d);
@@ -244,7 +243,7 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
   SVGEAR_LAUNCH_CHECK();
   AttnArgs a{qp, kp, vp, kbar, vbar, kbar16, vbar16, q_offsets, k_offsets, mask_bits, row_ptr, col_idx,
              tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr,
-             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse};
+             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part};
   if (dt == SVGEAR_F32) {
     dim3 grid(max_tiles, BH);
     if (d == 64)
@@ -266,4 +265,49 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
   }
   const unsigned total = (unsigned)align_up((size_t)BH * max_tiles, 8);
   return launch_attn_bf16(a, d, total, s);
+}
+
+extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
+                                       const float* kbar, const float* vbar, const int32_t* q_offsets,
+                                       const int32_t* k_offsets, const uint32_t* mask_bits, const int32_t* row_ptr,
+                                       const int32_t* col_idx, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
+                                       int Ck, float scale, void* op, float* lse, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  return attn_run(qp, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d, Cq,
+                  Ck, scale, op, lse, ws, ws_bytes, stream, 0);
+}
+
+extern "C" size_t svgear_sparse_attn_two_stage_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
+                                                         int Ck) {
+  const size_t base = svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck);
+  if (base == 0) return 0;
+  const size_t BH = (size_t)B * H;
+  return align_up(base, 256) + 2 * align_up(BH * Nq * d * 2, 256) + 2 * align_up(BH * Nq * 4, 256);
+}
+
+extern "C" int svgear_sparse_attn_two_stage(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
+                                            const float* kbar, const float* vbar, const int32_t* q_offsets,
+                                            const int32_t* k_offsets, const uint32_t* mask_bits,
+                                            const int32_t* row_ptr, const int32_t* col_idx, int B, int H, int64_t Nq,
+                                            int64_t Nk, int d, int Cq, int Ck, float scale, void* op, float* lse,
+                                            void* ws, size_t ws_bytes, void* stream) {
+  if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || Cq <= 0 || Ck <= 0 || !op) return SVGEAR_ERR_INVALID;
+  if (!(dt == SVGEAR_BF16 && d == 128)) return SVGEAR_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < svgear_sparse_attn_two_stage_workspace(B, H, Nq, Nk, d, Cq, Ck)) return SVGEAR_ERR_WORKSPACE;
+  const size_t base = align_up(svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck), 256);
+  const size_t BH = (size_t)B * H;
+  Workspace w(static_cast<char*>(ws) + base, ws_bytes - base);
+  bf16_t* o_r = w.take<bf16_t>(BH * Nq * d);
+  bf16_t* o_c = w.take<bf16_t>(BH * Nq * d);
+  float* lse_r = w.take<float>(BH * Nq);
+  float* lse_c = w.take<float>(BH * Nq);
+  if (!w.ok()) return SVGEAR_ERR_WORKSPACE;
+  int rc = attn_run(qp, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d,
+                    Cq, Ck, scale, o_r, lse_r, ws, base, stream, 1);
+  if (rc != SVGEAR_OK) return rc;
+  rc = attn_run(qp, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d, Cq,
+                Ck, scale, o_c, lse_c, ws, base, stream, 2);
+  if (rc != SVGEAR_OK) return rc;
+  return launch_merge(o_r, lse_r, o_c, lse_c, (int64_t)BH * Nq, d, static_cast<bf16_t*>(op), lse,
+                      static_cast<hipStream_t>(stream));
 }

@@ -524,9 +524,10 @@ attn_bf16_d128_kernel(AttnArgs p) {
     lw[b] = v;
   }
   __syncthreads();
-  const int n_r = __builtin_amdgcn_readfirstlane(vstart[ne]);  // wave-uniform: loop bounds in SGPRs
+  // (part 2 leaves the routed keys out, part 1 the centroid tiles: the two-stage form)
+  const int n_r = p.part == 2 ? 0 : __builtin_amdgcn_readfirstlane(vstart[ne]);  // wave-uniform
   const int nt_r = (n_r + BN - 1) / BN;
-  const int nt_c = (a < Cq) ? (Ck + BN - 1) / BN : 0;
+  const int nt_c = (a < Cq && p.part != 1) ? (Ck + BN - 1) / BN : 0;
   const int T = nt_r + nt_c;
   const int nt_full = n_r / BN;  // routed tiles with all 64 keys valid
   if (tid < BN) rag_bias[tid] = (nt_full * BN + tid < n_r) ? 0.f : -INFINITY;
@@ -1019,6 +1020,45 @@ int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
   a.sched_a = sched_a;
   a.sched_row0 = sched_row0;
   a.sched_x = sched_x;
+  return SVGEAR_OK;
+}
+
+// Merge of two partial softmax results over disjoint key sets (Algorithm 2's merge step):
+// one thread per 8 output elements.
+__global__ void __launch_bounds__(256)
+merge_kernel(const bf16_t* __restrict__ o1, const float* __restrict__ lse1, const bf16_t* __restrict__ o2,
+             const float* __restrict__ lse2, int64_t rows, int d, bf16_t* __restrict__ out,
+             float* __restrict__ lse) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (row, group of 8 dims)
+  const int per_row = d / 8;
+  if (i >= rows * per_row) return;
+  const int64_t row = i / per_row;
+  const float a = lse1[row], b = lse2[row];
+  const float m = fmaxf(a, b);
+  float w1 = 0.f, w2 = 0.f;
+  if (m > -INFINITY) {
+    w1 = expf(a - m);
+    w2 = expf(b - m);
+  }
+  const float den = w1 + w2;
+  const float s1 = den > 0.f ? w1 / den : 0.f, s2 = den > 0.f ? w2 / den : 0.f;
+  const uint4 x = *reinterpret_cast<const uint4*>(o1 + i * 8), y = *reinterpret_cast<const uint4*>(o2 + i * 8);
+  const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+  uint32_t r[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const float lo = s1 * __uint_as_float(xs[k] << 16) + s2 * __uint_as_float(ys[k] << 16);
+    const float hi = s1 * __uint_as_float(xs[k] & 0xffff0000u) + s2 * __uint_as_float(ys[k] & 0xffff0000u);
+    r[k] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  }
+  *reinterpret_cast<uint4*>(out + i * 8) = make_uint4(r[0], r[1], r[2], r[3]);
+  if (lse && (i % per_row) == 0) lse[row] = den > 0.f ? m + logf(den) : -INFINITY;
+}
+
+int launch_merge(const bf16_t* o1, const float* lse1, const bf16_t* o2, const float* lse2, int64_t rows, int d,
+                 bf16_t* out, float* lse, hipStream_t s) {
+  merge_kernel<<<(unsigned)ceil_div(rows * (d / 8), 256), 256, 0, s>>>(o1, lse1, o2, lse2, rows, d, out, lse);
+  SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;
 }
 

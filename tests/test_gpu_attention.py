@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 1e-2}  # relative L2 error of the attention output
 
 
-def _run_stage(wl, Q, K, V, refs, masks):
+def _run_stage(wl, Q, K, V, refs, masks, two_stage=False):
     """Feeds the oracle's clustering and the given masks to the GPU attention stage."""
     B, H = Q.shape[:2]
     Cq, Ck = wl.Cq, wl.Ck
@@ -34,7 +34,7 @@ def _run_stage(wl, Q, K, V, refs, masks):
                                                       for h in range(H)]) for b in range(B)]).to(dev())
     Qp, Kp, Vp = gather(Q, "perm_q"), gather(K, "perm_k"), gather(V, "perm_k")
     op, lse = sv.sparse_attn_comp(Qp, Kp, Vp, kbar, vbar, qoff, koff, bits, row_ptr, col_idx, orc.scale_of(wl.d),
-                                  want_lse=True)
+                                  want_lse=True, two_stage=two_stage)
     torch.cuda.synchronize()
     return Qp, Kp, Vp, op, lse
 
@@ -85,6 +85,37 @@ def test_attention_stage_matches_oracle(name, mode):
                 L = (to_np(Qp[b, h]).astype(np.float64) @ to_np(Kp[b, h]).astype(np.float64).T) * orc.scale_of(wl.d)
                 lse_ref = np.log(np.exp(L - L.max(1, keepdims=True)).sum(1)) + L.max(1)
                 assert np.allclose(to_np(lse[b, h]), lse_ref, atol=2e-2 if wl.dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("name", ["mini_video", "mini_video_tail", "mini_manyq", "mini_manyk"])
+@pytest.mark.parametrize("mode", ["routed", "none", "all"])
+def test_two_stage_form_matches_oracle_and_fused_kernel(name, mode):
+    """Algorithm 2's form on the GPU (routed pass, compensation pass, merge; bf16, d = 128)
+    against the oracle's literal evaluation and against the fused kernel, output and LSE."""
+    wl = get_workload(name)
+    Q, K, V = make_qkv(wl, "cpu")
+    B, H = Q.shape[:2]
+    refs = [[oracle_head(Q, K, V, b, h, wl, iters=3) for h in range(H)] for b in range(B)]
+    masks = [[None] * H for _ in range(B)]
+    for b in range(B):
+        for h in range(H):
+            base = full_mask(refs[b][h]["mask"], wl.Cq, wl.Ck)
+            forced = np.zeros_like(base)
+            forced[wl.Cq, :] = True
+            forced[:, wl.Ck] = True
+            nonempty = np.outer(np.diff(refs[b][h]["qoff"]) > 0, np.diff(refs[b][h]["koff"]) > 0)
+            m = np.ones_like(base) if mode == "all" else (forced.copy() if mode == "none" else base)
+            masks[b][h] = m & nonempty
+    Qp, Kp, Vp, op2, lse2 = _run_stage(wl, Q, K, V, refs, masks, two_stage=True)
+    _, _, _, op1, lse1 = _run_stage(wl, Q, K, V, refs, masks)
+    for b in range(B):
+        for h in range(H):
+            o_ref = _oracle_stage(wl, refs[b][h], to_np(Qp[b, h]), to_np(Kp[b, h]), to_np(Vp[b, h]), masks[b][h])
+            assert rel_l2(to_np(op2[b, h]), o_ref) <= TOL[wl.dtype], f"{name}/{mode} head {b},{h}"
+            assert rel_l2(to_np(op2[b, h]), to_np(op1[b, h])) <= TOL[wl.dtype]
+            l1, l2 = to_np(lse1[b, h]), to_np(lse2[b, h])
+            fin = np.isfinite(l1)
+            assert np.array_equal(fin, np.isfinite(l2)) and np.allclose(l1[fin], l2[fin], atol=2e-2)
 
 
 def test_identical_keys_per_cluster_compensation_exact_on_gpu():
