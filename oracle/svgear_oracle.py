@@ -14,6 +14,8 @@ Appendix "Kernel Implementation Details"):
   probe_errors    Eq. (7) (value-aware) or Eq. (5) (plain) summed over each block, with the
                   per-row stabiliser of Algorithm 1 (first line: m_i = max_j S_ij).
   route           "Error-Aware Routing": greedy by error-to-size ratio under the budget.
+  top_p_row_budgets  Experiments, "Implementation": one adaptive budget per query cluster (a
+                  labelled reading: the paper inherits the rule and does not define it).
   attention_comp  Eq. (1) and Eq. (6) evaluated literally.
 
 Readings taken where the paper is silent or inconsistent are listed next to each function.
@@ -241,7 +243,7 @@ def probe_errors_streaming(qbar, kbar, vbar, Kp, Vp, k_offsets, scale: float):
 
 
 def route(scores, q_sizes, k_sizes, budget: int, per_row: bool = False,
-          n_tail_q: int = 0, n_tail_k: int = 0):
+          n_tail_q: int = 0, n_tail_k: int = 0, row_budgets=None):
     """Greedy error-to-cost routing under a cost budget ("Error-Aware Routing").
 
     Blocks with both sizes non-zero are ordered by score descending (NaN counts as +inf),
@@ -256,7 +258,9 @@ def route(scores, q_sizes, k_sizes, budget: int, per_row: bool = False,
 
     per_row=True applies the same rule independently to each query cluster a with budget
     floor(budget * |q_a| / Nq_total) (the granularity of the paper's implementation,
-    Experiments, "Implementation").
+    Experiments, "Implementation"). row_budgets (one integer per query cluster, e.g. from
+    top_p_row_budgets) replaces that split: row a then routes clustered blocks up to
+    row_budgets[a]; the forced tail column comes on top and is not charged to it.
 
     Returns (mask bool [R, Cc], row_ptr i32 [R+1], col_idx i32, routed_cost int) with
     R = Cq + (n_tail_q > 0), Cc = Ck + (n_tail_k > 0); col_idx ascending within a row.
@@ -293,11 +297,14 @@ def route(scores, q_sizes, k_sizes, budget: int, per_row: bool = False,
             mask[a, b] = True
         return spent
 
-    if per_row:
+    if per_row or row_budgets is not None:
         for a in range(Cq):
             if qs[a] == 0:
                 continue
-            rem = max((int(budget) * qs[a]) // max(nq_total, 1) - row_forced[a], 0)
+            if row_budgets is not None:
+                rem = max(int(row_budgets[a]), 0)
+            else:
+                rem = max((int(budget) * qs[a]) // max(nq_total, 1) - row_forced[a], 0)
             routed_cost += greedy([(a, b) for b in range(Ck) if ks[b] > 0], rem)
     else:
         rem = max(int(budget) - routed_cost, 0)
@@ -309,6 +316,55 @@ def route(scores, q_sizes, k_sizes, budget: int, per_row: bool = False,
     col_idx = np.concatenate([np.nonzero(mask[a])[0] for a in range(R)]).astype(np.int32) \
         if R else np.zeros(0, np.int32)
     return mask, row_ptr, col_idx, int(routed_cost)
+
+
+TOP_P_WEIGHT_BITS = 20
+
+
+def top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p: float, scale: float):
+    """Adaptive per-query-cluster budgets (Experiments, "Implementation": the method inherits
+    a top-p budget allocation and routes per query cluster; hyper-parameter table, "TopP").
+
+    The paper does not define the rule. Reading taken (a labelled guess): for query cluster a,
+    the non-empty key clusters carry the centroid attention mass
+        mass_b = |k_b| exp(qbar_a . kbar_b * scale - m_a),  m_a the largest such logit,
+    i.e. the share of a centroid query's softmax that falls on cluster b when every key sits at
+    its centroid. Masses are taken in units of 2^-20 (w_b = floor(mass_b 2^20), an integer, so
+    that sums do not depend on the order of addition); clusters are ordered by w_b descending,
+    equal ones by ascending b; the prefix kept is the shortest whose summed weight reaches
+    ceil(p * sum_b w_b). The budget of row a is the cost of exact attention over that prefix,
+    |q_a| * sum_{b kept} |k_b| query-key pairs; error-aware routing then spends it on the
+    blocks of row a with the largest error-to-cost ratio.
+
+    Returns (budgets int64 [Cq], n_keep int32 [Cq]); empty query clusters get 0."""
+    qbar, kbar = np.asarray(qbar, np.float64), np.asarray(kbar, np.float64)
+    Cq, Ck = qbar.shape[0], kbar.shape[0]
+    qs = [int(v) for v in q_sizes[:Cq]]
+    ks = [int(v) for v in k_sizes[:Ck]]
+    p = float(np.float32(p))
+    budgets = np.zeros(Cq, dtype=np.int64)
+    n_keep = np.zeros(Cq, dtype=np.int32)
+    live = [b for b in range(Ck) if ks[b] > 0]
+    for a in range(Cq):
+        if qs[a] == 0 or not live:
+            continue
+        logit = {b: float(qbar[a] @ kbar[b]) * scale for b in live}
+        m = max(logit.values())
+        w = {b: int(np.floor(ks[b] * np.exp(logit[b] - m) * float(1 << TOP_P_WEIGHT_BITS))) for b in live}
+        total = sum(w.values())
+        need = max(int(np.ceil(p * float(total))), 1)
+        run = 0
+        keys = 0
+        for n, b in enumerate(sorted(live, key=lambda b: (-w[b], b)), start=1):
+            run += w[b]
+            keys += ks[b]
+            if run >= need:
+                n_keep[a] = n
+                break
+        else:
+            n_keep[a] = len(live)
+        budgets[a] = qs[a] * keys
+    return budgets, n_keep
 
 
 # --------------------------------------------------------------------------- attention
@@ -408,7 +464,7 @@ def scale_of(d: int) -> float:
 
 
 def hot_path_head(Q, K, V, init_q, init_k, iters: int, budget: int, n_tail: int = 0,
-                  value_aware: bool = True, per_row: bool = False):
+                  value_aware: bool = True, per_row: bool = False, top_p: Optional[float] = None):
     """All stages for one head, in the order the method runs them; returns a dict with
     every intermediate (used by the end-to-end parity test and the cpu_baseline timing).
     Q, K, V are [N, d] arrays (any float dtype holding the exact input values)."""
@@ -423,7 +479,8 @@ def hot_path_head(Q, K, V, init_q, init_k, iters: int, budget: int, n_tail: int 
     perm_k, koff = permute(lab_k, Ck, n_tail)
     Qp, Kp, Vp = Q32[perm_q], K32[perm_k], V32[perm_k]
     E, scores, m = probe_errors(qbar, kbar, vbar, Kp, Vp, koff, scale, value_aware)
-    mask, row_ptr, col_idx, cost = route(scores, qcnt, kcnt, budget, per_row, n_tail, n_tail)
+    row_budgets = top_p_row_budgets(qbar, kbar, qcnt, kcnt, top_p, scale)[0] if top_p is not None else None
+    mask, row_ptr, col_idx, cost = route(scores, qcnt, kcnt, budget, per_row, n_tail, n_tail, row_budgets)
     lq = np.repeat(np.arange(Cq + 1), np.diff(qoff))
     lk = np.repeat(np.arange(Ck + 1), np.diff(koff))
     kb = np.concatenate([kbar, np.zeros((1, d), np.float32)]) if n_tail else kbar

@@ -75,3 +75,18 @@ def test_more_query_clusters_tighten_clustering_error():
     mse = [r[2] for r in rows]
     assert dq[0] > dq[1] > dq[2]
     assert mse[0] > mse[2]
+
+
+def test_top_p_mask_of_the_study_keeps_as_many_clusters_as_the_row_budget_rule():
+    # the float-valued selection used in the study and the integer-unit budget rule of the
+    # oracle are two codings of the same reading; on generic data they keep the same prefix
+    from oracle import svgear_oracle as orc
+    rng = np.random.default_rng(5)
+    qbar, kbar = rng.standard_normal((7, 16)), rng.standard_normal((13, 16))
+    k_sizes = rng.integers(0, 40, 13)
+    q_sizes = rng.integers(1, 9, 7)
+    for p in (0.4, 0.7, 0.9):
+        mask = ea.top_p_mask(qbar, kbar, k_sizes, p, 0.25)
+        budgets, n_keep = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p, 0.25)
+        assert np.array_equal(mask.sum(axis=1), n_keep)
+        assert np.array_equal((mask * k_sizes[None, :]).sum(axis=1) * q_sizes, budgets)

@@ -233,3 +233,129 @@ def test_route_per_row_budgets():
         m1, _, _, c1 = orc.route(scores[a: a + 1], [qs[a]], ks, row_budget)
         assert m1[0].tolist() == mask[a].tolist()
     assert cost == int((np.outer(qs, ks) * mask).sum())
+
+
+# ------------------------------------------------------------------ top-p row budgets (reading)
+
+
+def _top_p_case(seed, Cq=6, Ck=11, d=8, empty=(4,)):
+    rng = np.random.default_rng(seed)
+    qbar = rng.standard_normal((Cq, d)) * 1.5
+    kbar = rng.standard_normal((Ck, d)) * 1.5
+    q_sizes = rng.integers(1, 9, Cq)
+    k_sizes = rng.integers(1, 30, Ck)
+    for b in empty:
+        k_sizes[b] = 0
+    return qbar, kbar, q_sizes, k_sizes
+
+
+def test_top_p_budget_is_cost_of_softmax_mass_prefix_bruteforce():
+    # brute force over every subset size: the kept set is the n heaviest clusters (centroid
+    # softmax mass of a key set = sum of |k_b| softmax terms), n the least that reaches p
+    scale = 0.4
+    for seed in range(6):
+        qbar, kbar, q_sizes, k_sizes = _top_p_case(seed)
+        for p in (0.3, 0.6, 0.9):
+            budgets, n_keep = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p, scale)
+            for a in range(qbar.shape[0]):
+                logits = np.repeat(qbar[a] @ kbar.T * scale, k_sizes)  # one pseudo-key per key of a cluster
+                owner = np.repeat(np.arange(kbar.shape[0]), k_sizes)
+                soft = np.exp(logits - logits.max())
+                soft /= soft.sum()
+                share = np.bincount(owner, weights=soft, minlength=kbar.shape[0])
+                order = np.argsort(-share, kind="stable")
+                n = 1
+                while share[order[:n]].sum() < p - 1e-9:
+                    n += 1
+                # generic data: no share sits within 1e-5 of the threshold, so the 2^-20 units do not matter
+                assert abs(share[order[:n]].sum() - p) > 1e-5
+                assert n_keep[a] == n
+                assert budgets[a] == q_sizes[a] * k_sizes[order[:n]].sum()
+
+
+def test_top_p_uniform_logits_closed_form():
+    # equal centroids, equal sizes: every cluster has the same mass, n = ceil(p Ck), lowest indices
+    Ck, Cq, d = 10, 3, 4
+    kbar = np.tile(np.arange(1.0, d + 1), (Ck, 1))
+    qbar = np.ones((Cq, d))
+    q_sizes = np.array([2, 0, 5])
+    k_sizes = np.full(Ck, 7)
+    for p, n in ((0.05, 1), (0.09, 1), (0.11, 2), (0.5, 5), (0.95, 10), (1.0, 10)):
+        budgets, n_keep = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p, 0.5)
+        assert list(n_keep) == [n, 0, n]
+        assert list(budgets) == [2 * 7 * n, 0, 5 * 7 * n]
+
+
+def test_top_p_limits_monotone_and_empty_clusters():
+    qbar, kbar, q_sizes, k_sizes = _top_p_case(3, empty=(0, 7))
+    scale = 0.15
+    tiny, n_tiny = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, 1e-6, scale)
+    mass = k_sizes[None, :] * np.exp(qbar @ kbar.T * scale)
+    heaviest = mass.argmax(axis=1)
+    assert np.all(n_tiny == 1) and np.array_equal(tiny, q_sizes * k_sizes[heaviest])
+    full, n_full = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, 1.0, scale)
+    # p = 1 keeps every cluster whose mass is at least one unit of 2^-20; here all of them are
+    live = k_sizes > 0
+    assert (mass[:, live].min(axis=1) / mass.max(axis=1)).min() > 2.0 ** -18
+    assert np.all(n_full == (k_sizes > 0).sum()) and np.array_equal(full, q_sizes * k_sizes.sum())
+    prev = tiny
+    for p in np.linspace(0.05, 1.0, 20):
+        cur, _ = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, float(p), scale)
+        assert np.all(cur >= prev)
+        prev = cur
+    # a far-away cluster (mass below one unit) is never kept, even at p = 1
+    kbar2 = kbar.copy()
+    kbar2[5] = -40.0 * qbar[0] / np.linalg.norm(qbar[0])
+    _, n2 = orc.top_p_row_budgets(qbar[:1], kbar2, q_sizes[:1], k_sizes, 1.0, scale)
+    assert n2[0] == (k_sizes > 0).sum() - 1
+
+
+def test_top_p_query_size_scaling_and_key_cluster_relabelling():
+    # the kept prefix does not depend on |q_a| (the budget scales with it) nor on how the key
+    # clusters are numbered
+    qbar, kbar, q_sizes, k_sizes = _top_p_case(5, empty=())
+    b1, n1 = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, 0.7, 0.3)
+    b2, n2 = orc.top_p_row_budgets(qbar, kbar, 3 * q_sizes, k_sizes, 0.7, 0.3)
+    assert np.array_equal(n1, n2) and np.array_equal(3 * b1, b2)
+    perm = np.random.default_rng(0).permutation(kbar.shape[0])
+    b3, n3 = orc.top_p_row_budgets(qbar, kbar[perm], q_sizes, k_sizes[perm], 0.7, 0.3)
+    assert np.array_equal(n1, n3) and np.array_equal(b1, b3)
+
+
+def test_route_with_row_budgets_spends_each_rows_own_budget():
+    rng = np.random.default_rng(9)
+    Cq, Ck = 5, 9
+    scores = rng.random((Cq, Ck))
+    q_sizes = rng.integers(1, 6, Cq)
+    k_sizes = rng.integers(1, 12, Ck)
+    row_budgets = np.array([0, 10 ** 9, 37, 5, 60]) * 1
+    mask, row_ptr, col_idx, cost = orc.route(scores, q_sizes, k_sizes, 0, row_budgets=row_budgets, n_tail_k=4)
+    assert mask[:, Ck].all()  # forced tail column, on top of the row budgets
+    assert not mask[0, :Ck].any() and mask[1, :Ck].all()
+    total = 0
+    for a in range(Cq):
+        spent = 0
+        for b in np.argsort(-scores[a], kind="stable"):
+            c = q_sizes[a] * k_sizes[b]
+            if spent + c > row_budgets[a]:
+                break
+            spent += c
+            assert mask[a, b]
+        assert spent == (mask[a, :Ck] * q_sizes[a] * k_sizes).sum()
+        total += spent + q_sizes[a] * 4
+    assert cost == total
+
+
+def test_top_p_then_route_reproduces_top_p_selection_when_scores_are_the_masses():
+    # if the error ratio handed to the router is the mass per key, the router's order is the top-p
+    # order for equal-size key clusters, so the routed set is exactly the top-p prefix
+    rng = np.random.default_rng(11)
+    Cq, Ck, d = 4, 12, 6
+    qbar, kbar = rng.standard_normal((Cq, d)), rng.standard_normal((Ck, d))
+    q_sizes, k_sizes = rng.integers(1, 5, Cq), np.full(Ck, 6)
+    budgets, n_keep = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, 0.8, 0.5)
+    mass = np.exp(qbar @ kbar.T * 0.5)
+    mask = orc.route(mass, q_sizes, k_sizes, 0, row_budgets=budgets)[0]
+    for a in range(Cq):
+        top = np.argsort(-mass[a], kind="stable")[: n_keep[a]]
+        assert set(np.nonzero(mask[a])[0]) == set(top)
