@@ -238,9 +238,25 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
             row["rel_l2_vs_all_routed_plain_probe"] = rel_l2(attend(budget, sv.PROBE_PLAIN), o_dense)
             row["rel_l2_vs_all_routed_per_row_budget"] = rel_l2(attend(budget, sv.ROUTE_PER_ROW), o_dense)
         rows.append(row)
+    # adaptive per-query-cluster budgets (the top-p reading of the paper's implementation), with
+    # the one-budget-per-head rule at the same mean cost beside it
+    top_p_rows = []
+    for p in [0.3, 0.5, 0.7, 0.85]:
+        def probe_p():
+            return sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], 0, scale, top_p=p)
+        t_pr, pr = _time_ms(probe_p)
+        t_at, at = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
+                                                        pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale))
+        mean_cost = int(pr["routed_cost"].double().mean().item())
+        top_p_rows.append({"top_p": p, "achieved_density": mean_cost / float(wl.N) ** 2, "probe_route_ms": t_pr,
+                           "attention_ms": t_at,
+                           "layer_ms": base["kmeans"] + base["permute"] + base["unpermute"] + t_pr + t_at,
+                           "rel_l2_vs_all_routed": rel_l2(at[0], o_dense),
+                           "rel_l2_vs_all_routed_one_budget_same_cost": rel_l2(attend(mean_cost), o_dense)})
+        del at
     del o_dense
     out = {"mode": "sweep", "workload": wl.name, "kmeans_ms": base["kmeans"], "permute_ms": base["permute"],
-           "unpermute_ms": base["unpermute"], "sweep": rows}
+           "unpermute_ms": base["unpermute"], "sweep": rows, "top_p_sweep": top_p_rows}
     try:
         t_sd, _ = _time_ms(lambda: torch.nn.functional.scaled_dot_product_attention(Q, K, V), reps=2)
         out["torch_sdpa_dense_ms"] = t_sd

@@ -140,6 +140,33 @@ int svgear_probe_route(const float* qbar, const float* kbar, const float* vbar, 
                        int64_t* routed_cost, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * probe + route with one ADAPTIVE budget per query cluster (Experiments, "Implementation":
+ * the method inherits a top-p budget allocation, hyper-parameter "TopP", and routes per query
+ * cluster). The paper does not define that allocation; this entry point implements a stated
+ * reading of it, not a rule the paper prints:
+ *   for query cluster a, every non-empty key cluster b carries the centroid attention mass
+ *     mass_b = |k_b| exp(Sbar_ab - m_a)       (Sbar, m_a as in the probe above),
+ *   counted in integer units w_b = floor(mass_b * 2^20) (fp32 evaluation); clusters are ordered
+ *   by w_b descending, equal ones by ascending b; the shortest prefix whose summed weight
+ *   reaches ceil(top_p * sum_b w_b) (double arithmetic) is kept, and
+ *     row_budget[a] = |q_a| * sum over the kept b of |k_b|
+ *   query-key pairs. Row a then routes its clustered blocks by descending score exactly as
+ *   with SVGEAR_ROUTE_PER_ROW, up to row_budget[a]; the tail column and tail row are routed
+ *   in addition and are not charged to it.
+ * Arguments as svgear_probe_route, except: top_p in (0, 1] replaces budget_cost;
+ * row_budget [BH,Cq] int64 out. flags: SVGEAR_PROBE_PLAIN and SVGEAR_USE_GIVEN_SCORES are
+ * accepted (with given scores qbar and kbar are still read, for the masses);
+ * SVGEAR_ROUTE_PER_ROW is implied and must not be set. Workspace: svgear_probe_route_workspace.
+ */
+int svgear_probe_route_top_p(const float* qbar, const float* kbar, const float* vbar, const void* kp,
+                             const void* vp, svgear_dtype dt, const int32_t* q_offsets,
+                             const int32_t* k_offsets, int B, int H, int64_t Nq, int64_t Nk, int d,
+                             int Cq, int Ck, float top_p, float scale, unsigned flags, float* scores,
+                             uint32_t* mask_bits, int32_t* row_ptr, int32_t* col_idx,
+                             int64_t* routed_cost, int64_t* row_budget, void* ws, size_t ws_bytes,
+                             void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * fused block-sparse attention + centroid compensation (Eq. (1), Eq. (6); Algorithm 2).
  *
  * For every query row i of query cluster a, one softmax over

@@ -21,7 +21,9 @@ Appendix "Kernel Implementation Details"):
 Readings taken where the paper is silent or inconsistent are listed next to each function.
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py against closed forms,
-brute force or library routines; none is "parity unpinned".
+brute force or library routines. One caveat: top_p_row_budgets implements a reading of a rule
+the paper inherits without printing it; it is pinned to that stated definition and is "parity
+unpinned" with respect to whatever rule the paper's own implementation used.
 """
 from __future__ import annotations
 

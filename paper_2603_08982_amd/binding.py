@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "svgear_version", "svgear_last_hip_error",
     "svgear_kmeans_workspace", "svgear_kmeans",
     "svgear_permute_workspace", "svgear_permute",
-    "svgear_probe_route_workspace", "svgear_probe_route",
+    "svgear_probe_route_workspace", "svgear_probe_route", "svgear_probe_route_top_p",
     "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp",
     "svgear_sparse_attn_two_stage_workspace", "svgear_sparse_attn_two_stage",
     "svgear_unpermute",
@@ -70,6 +70,9 @@ def load_library():
     lib.svgear_probe_route.restype = _i
     lib.svgear_probe_route.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _i64, _i64, _i, _i, _i,
                                        _i64, _f, _u, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.svgear_probe_route_top_p.restype = _i
+    lib.svgear_probe_route_top_p.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _i64, _i64, _i, _i, _i,
+                                             _f, _f, _u, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.svgear_sparse_attn_comp_workspace.restype = _sz
     lib.svgear_sparse_attn_comp_workspace.argtypes = [_i, _i, _i64, _i64, _i, _i, _i]
     lib.svgear_sparse_attn_comp.restype = _i
@@ -175,8 +178,10 @@ def permute(labels: torch.Tensor, C: int, tensors: Sequence[torch.Tensor] = (), 
 
 
 def probe_route(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, budget_cost: int, scale: float,
-                flags: int = 0, scores: Optional[torch.Tensor] = None, Nq: Optional[int] = None):
-    """svgear_probe_route. Returns dict(scores, mask_bits, row_ptr, col_idx, routed_cost)."""
+                flags: int = 0, scores: Optional[torch.Tensor] = None, Nq: Optional[int] = None,
+                top_p: Optional[float] = None):
+    """svgear_probe_route, or svgear_probe_route_top_p when top_p is given (budget_cost is then
+    ignored). Returns dict(scores, mask_bits, row_ptr, col_idx, routed_cost[, row_budget])."""
     _need_gpu(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, scores)
     lib = load_library()
     B, H, Cq, d = qbar.shape
@@ -195,6 +200,16 @@ def probe_route(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, budget_cost: int
     ws = _ws(lib.svgear_probe_route_workspace(B, H, Nk, d, Cq, Ck), dev)
     for t in (qbar, kbar, vbar, kp, vp, q_offsets, k_offsets):
         assert t.is_contiguous()
+    if top_p is not None:
+        row_budget = torch.empty(B, H, Cq, dtype=torch.int64, device=dev)
+        rc = lib.svgear_probe_route_top_p(_ptr(qbar), _ptr(kbar), _ptr(vbar), _ptr(kp), _ptr(vp), _dt(kp),
+                                          _ptr(q_offsets), _ptr(k_offsets), B, H, Nq, Nk, d, Cq, Ck, float(top_p),
+                                          float(scale), int(flags), _ptr(scores), _ptr(mask_bits), _ptr(row_ptr),
+                                          _ptr(col_idx), _ptr(routed_cost), _ptr(row_budget), _ptr(ws), ws.numel(),
+                                          _stream())
+        _check(rc, "svgear_probe_route_top_p")
+        return dict(scores=scores, mask_bits=mask_bits, row_ptr=row_ptr, col_idx=col_idx, routed_cost=routed_cost,
+                    row_budget=row_budget)
     rc = lib.svgear_probe_route(_ptr(qbar), _ptr(kbar), _ptr(vbar), _ptr(kp), _ptr(vp), _dt(kp), _ptr(q_offsets),
                                 _ptr(k_offsets), B, H, Nq, Nk, d, Cq, Ck, int(budget_cost), float(scale),
                                 int(flags), _ptr(scores), _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx),
@@ -274,13 +289,14 @@ def run_pair(fn_side, fn_main):
 
 
 def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tail: int = 0, flags: int = 0,
-                    scale: Optional[float] = None, overlap: bool = True):
+                    scale: Optional[float] = None, overlap: bool = True, top_p: Optional[float] = None):
     """One pass of the whole hot path over a batch of heads: the five library calls in order
     (with overlap=True the Q and the K/V call of k-means, and then of the permutation, run
     side by side on two streams).
 
     init_q [B,H,Cq,d], init_k [B,H,Ck,d] fp32 are the starting centroids (updated in place,
-    so a caller can carry them to the next denoising step). Returns (O, intermediates)."""
+    so a caller can carry them to the next denoising step). With top_p the routing budget is
+    the adaptive per-query-cluster one and budget_cost is ignored. Returns (O, intermediates)."""
     B, H, N, d = Q.shape
     if scale is None:
         scale = float(d) ** -0.5
@@ -290,7 +306,7 @@ def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tai
                                                  lambda: kmeans(K, init_k, iters, n_tail, x2=V))
     (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = pair(lambda: permute(lab_q, Cq, [Q], n_tail),
                                                            lambda: permute(lab_k, Ck, [K, V], n_tail))
-    r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags)
+    r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
     Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
     O = unpermute(Op, perm_q)
     r.update(lab_q=lab_q, lab_k=lab_k, qcnt=qcnt, kcnt=kcnt, qbar=init_q, kbar=init_k, vbar=vbar, perm_q=perm_q,

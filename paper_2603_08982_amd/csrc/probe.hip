@@ -318,6 +318,17 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
 
 }  // namespace
 
+// Centroid logits and their row maxima alone (no block errors).
+int run_sbar(const float* qbar, const float* kbar, const int32_t* k_offsets, int BH, int d, int Cq, int Ck,
+             float scale, float* sbar, float* mrow, hipStream_t s) {
+  if (d == 64)
+    sbar_kernel<64><<<dim3(Cq, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow, nullptr);
+  else
+    sbar_kernel<128><<<dim3(Cq, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow, nullptr);
+  SVGEAR_LAUNCH_CHECK();
+  return SVGEAR_OK;
+}
+
 int run_probe(const float* qbar, const float* kbar, const float* vbar, const void* kp, const void* vp,
               svgear_dtype dt, const int32_t* k_offsets, int BH, int64_t Nk, int d, int Cq, int Ck, float scale,
               bool value_aware, float* scores, float* sbar, float* mrow, bf16_t* q3, float* nd, float* dd,

@@ -8,6 +8,9 @@
 // the budget. Each block gets a unique 64-bit key that is monotone in that order; an
 // 8-pass, most-significant-byte-first radix descent over cost histograms finds the key K*
 // of the cut exactly (integer arithmetic only), and block (a,b) is routed iff key > K*.
+//
+// The adaptive per-query-cluster budgets (a reading of the top-p allocation the paper
+// inherits and does not define) use the same descent over integer mass weights.
 #include "common.h"
 
 namespace svgear {
@@ -17,9 +20,15 @@ int run_probe(const float* qbar, const float* kbar, const float* vbar, const voi
               bool value_aware, float* scores, float* sbar, float* mrow, bf16_t* q3, float* nd, float* dd,
               hipStream_t s);
 
+int run_sbar(const float* qbar, const float* kbar, const int32_t* k_offsets, int BH, int d, int Cq, int Ck,
+             float scale, float* sbar, float* mrow, hipStream_t s);
+
 namespace {
 
 constexpr int kSelThreads = 1024;
+constexpr int kTopPThreads = 256;
+constexpr int kTopPWeightBits = 20;  // masses are counted in units of 2^-20
+constexpr int kTopPIndexBits = 13;   // Ck <= 8192
 
 // Larger score -> larger key; among equal scores lower linear index -> larger key.
 __device__ __forceinline__ uint64_t block_key(float score, uint32_t idx) {
@@ -30,15 +39,70 @@ __device__ __forceinline__ uint64_t block_key(float score, uint32_t idx) {
   return ((uint64_t)u << 32) | (uint64_t)(0xFFFFFFFFu - idx);
 }
 
-// grid (nseg, BH): nseg = 1 (one budget per head) or Cq (one per query cluster).
+struct CutState {
+  unsigned long long hist[256];
+  unsigned long long prefix;
+  long long remaining;
+  int done;
+};
+
+// Walks n_items items in descending key order (keys unique) and returns the key of the first
+// one whose inclusive cumulative weight exceeds rem, or 0 if every item fits. visit(it, key,
+// weight) returns false for items that do not take part. Called by all threads of the block.
+template <int THREADS, class Visit>
+__device__ __forceinline__ unsigned long long radix_cut(CutState& st, long long rem, int64_t n_items, Visit visit) {
+  if (threadIdx.x == 0) {
+    st.remaining = rem > 0 ? rem : 0;
+    st.prefix = 0ull;
+    st.done = 0;
+  }
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+    for (int i = threadIdx.x; i < 256; i += THREADS) st.hist[i] = 0ull;
+    __syncthreads();
+    if (st.done) break;
+    const unsigned long long prefix = st.prefix;
+    for (int64_t it = threadIdx.x; it < n_items; it += THREADS) {
+      uint64_t key;
+      unsigned long long weight;
+      if (!visit(it, key, weight)) continue;
+      if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
+      atomicAdd(&st.hist[(key >> shift) & 255u], weight);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      long long cum = 0;
+      const long long left = st.remaining;
+      int found = -1;
+      for (int dg = 255; dg >= 0; --dg) {
+        const long long h = (long long)st.hist[dg];
+        if (cum + h > left) {
+          found = dg;
+          break;
+        }
+        cum += h;
+      }
+      if (found < 0) {  // everything fits (can only happen on the first pass)
+        st.done = 1;
+        st.prefix = 0ull;
+      } else {
+        st.remaining = left - cum;
+        st.prefix = (prefix << 8) | (unsigned long long)found;
+      }
+    }
+    __syncthreads();
+  }
+  __syncthreads();
+  return st.prefix;
+}
+
+// grid (nseg, BH): nseg = 1 (one budget per head) or Cq (one per query cluster; row_budget,
+// if given, holds each cluster's budget for its clustered blocks, the tail column on top).
 __global__ void __launch_bounds__(kSelThreads)
 select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_offsets,
               const int32_t* __restrict__ k_offsets, int Cq, int Ck, int64_t budget, int per_row,
-              uint64_t* __restrict__ kstar) {
-  __shared__ unsigned long long hist[256];
-  __shared__ unsigned long long sh_prefix;
-  __shared__ long long sh_remaining;
-  __shared__ int sh_done;
+              const int64_t* __restrict__ row_budget, uint64_t* __restrict__ kstar) {
+  __shared__ CutState st;
   const int seg = blockIdx.x, bh = blockIdx.y;
   const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
   const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
@@ -47,57 +111,87 @@ select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_of
   const int64_t tq = qo[Cq + 1] - qo[Cq], tk = ko[Ck + 1] - ko[Ck];
   const int a_lo = per_row ? seg : 0, a_hi = per_row ? seg + 1 : Cq;
   const int64_t n_items = (int64_t)(a_hi - a_lo) * Ck;
-  if (threadIdx.x == 0) {
-    long long rem;
-    if (per_row) {
-      const int64_t qa = qo[seg + 1] - qo[seg];
-      rem = (budget * qa) / (Nq > 0 ? Nq : 1) - qa * tk;
-    } else {
-      rem = budget - (tq * Nk + (Nq - tq) * tk);
-    }
-    sh_remaining = rem > 0 ? rem : 0;
-    sh_prefix = 0ull;
-    sh_done = 0;
+  long long rem;
+  if (row_budget) {
+    rem = row_budget[(int64_t)bh * Cq + seg];
+  } else if (per_row) {
+    const int64_t qa = qo[seg + 1] - qo[seg];
+    rem = (budget * qa) / (Nq > 0 ? Nq : 1) - qa * tk;
+  } else {
+    rem = budget - (tq * Nk + (Nq - tq) * tk);
   }
-  for (int pass = 0; pass < 8; ++pass) {
-    const int shift = 56 - 8 * pass;
-    for (int i = threadIdx.x; i < 256; i += kSelThreads) hist[i] = 0ull;
-    __syncthreads();
-    if (sh_done) break;
-    const unsigned long long prefix = sh_prefix;
-    for (int64_t it = threadIdx.x; it < n_items; it += kSelThreads) {
-      const int a = a_lo + (int)(it / Ck), b = (int)(it % Ck);
-      const int64_t cost = (int64_t)(qo[a + 1] - qo[a]) * (int64_t)(ko[b + 1] - ko[b]);
-      if (cost <= 0) continue;
-      const uint64_t key = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b));
-      if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
-      atomicAdd(&hist[(key >> shift) & 255u], (unsigned long long)cost);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      long long cum = 0;
-      const long long rem = sh_remaining;
-      int found = -1;
-      for (int dg = 255; dg >= 0; --dg) {
-        const long long h = (long long)hist[dg];
-        if (cum + h > rem) {
-          found = dg;
-          break;
-        }
-        cum += h;
-      }
-      if (found < 0) {  // everything fits (can only happen on the first pass)
-        sh_done = 1;
-        sh_prefix = 0ull;
-      } else {
-        sh_remaining = rem - cum;
-        sh_prefix = (prefix << 8) | (unsigned long long)found;
-      }
-    }
-    __syncthreads();
+  const unsigned long long cut = radix_cut<kSelThreads>(st, rem, n_items, [&](int64_t it, uint64_t& key,
+                                                                              unsigned long long& weight) {
+    const int a = a_lo + (int)(it / Ck), b = (int)(it % Ck);
+    const int64_t cost = (int64_t)(qo[a + 1] - qo[a]) * (int64_t)(ko[b + 1] - ko[b]);
+    if (cost <= 0) return false;
+    key = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b));
+    weight = (unsigned long long)cost;
+    return true;
+  });
+  if (threadIdx.x == 0) kstar[(int64_t)bh * (per_row ? Cq : 1) + seg] = cut;
+}
+
+// Adaptive budget of query cluster a (grid (Cq, BH)): the non-empty key clusters carry the
+// centroid attention mass |k_b| exp(Sbar_ab - m_a), counted in integer units of 2^-20 so that
+// sums are exact in any order; ordered by weight descending (ties: lower b first), the
+// shortest prefix whose weight reaches ceil(top_p * total) is kept, and the budget is the
+// cost |q_a| * sum |k_b| of exact attention over it.
+__global__ void __launch_bounds__(kTopPThreads)
+top_p_budget_kernel(const float* __restrict__ sbar, const float* __restrict__ mrow,
+                    const int32_t* __restrict__ q_offsets, const int32_t* __restrict__ k_offsets, int Cq, int Ck,
+                    float top_p, int64_t* __restrict__ row_budget) {
+  extern __shared__ unsigned long long wgt[];  // Ck
+  __shared__ CutState st;
+  __shared__ unsigned long long sh_total, sh_keys;
+  const int a = blockIdx.x, bh = blockIdx.y;
+  const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
+  const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
+  const int64_t qa = qo[a + 1] - qo[a];
+  if (qa <= 0) {
+    if (threadIdx.x == 0) row_budget[(int64_t)bh * Cq + a] = 0;
+    return;
+  }
+  if (threadIdx.x == 0) {
+    sh_total = 0ull;
+    sh_keys = 0ull;
   }
   __syncthreads();
-  if (threadIdx.x == 0) kstar[(int64_t)bh * (per_row ? Cq : 1) + seg] = sh_prefix;
+  const float* sr = sbar + ((int64_t)bh * Cq + a) * Ck;
+  const float m = mrow[(int64_t)bh * Cq + a];
+  unsigned long long part = 0ull;
+  for (int b = threadIdx.x; b < Ck; b += kTopPThreads) {
+    const int32_t kb = ko[b + 1] - ko[b];
+    unsigned long long w = 0ull;
+    if (kb > 0) {
+      const float mass = (float)kb * expf(sr[b] - m) * (float)(1 << kTopPWeightBits);
+      if (mass >= 1.f) w = (unsigned long long)mass;  // also drops NaN
+    }
+    wgt[b] = w;
+    part += w;
+  }
+  if (part) atomicAdd(&sh_total, part);
+  __syncthreads();
+  const unsigned long long total = sh_total;
+  const double want = ceil((double)top_p * (double)total);
+  const long long need = want >= 1.0 ? (long long)want : 1ll;
+  auto key_of = [&](int b) { return (wgt[b] << kTopPIndexBits) | (unsigned long long)((1 << kTopPIndexBits) - 1 - b); };
+  const unsigned long long cut = radix_cut<kTopPThreads>(st, need - 1, Ck, [&](int64_t it, uint64_t& key,
+                                                                               unsigned long long& weight) {
+    const int b = (int)it;
+    if (ko[b + 1] <= ko[b]) return false;
+    key = key_of(b);
+    weight = wgt[b];
+    return true;
+  });
+  unsigned long long keys = 0ull;
+  for (int b = threadIdx.x; b < Ck; b += kTopPThreads) {
+    const int32_t kb = ko[b + 1] - ko[b];
+    if (kb > 0 && key_of(b) >= cut) keys += (unsigned long long)kb;
+  }
+  if (keys) atomicAdd(&sh_keys, keys);
+  __syncthreads();
+  if (threadIdx.x == 0) row_budget[(int64_t)bh * Cq + a] = qa * (int64_t)sh_keys;
 }
 
 // grid (BH). Builds the bit mask, the CSR lists and the routed cost from K*.
@@ -182,21 +276,29 @@ extern "C" size_t svgear_probe_route_workspace(int B, int H, int64_t Nk, int d, 
          align_up(BH * align_up(Cq, 32) * d * 3 * 2, 256) + 2 * align_up(BH * probe_stat_stride(Nk) * 4, 256);
 }
 
-extern "C" int svgear_probe_route(const float* qbar, const float* kbar, const float* vbar, const void* kp,
-                                  const void* vp, svgear_dtype dt, const int32_t* q_offsets,
-                                  const int32_t* k_offsets, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
-                                  int Ck, int64_t budget_cost, float scale, unsigned flags, float* scores,
-                                  uint32_t* mask_bits, int32_t* row_ptr, int32_t* col_idx, int64_t* routed_cost,
-                                  void* ws, size_t ws_bytes, void* stream) {
+namespace {
+
+// top_p < 0: budget_cost rules (per head or per query cluster); otherwise adaptive row budgets.
+int probe_route_impl(const float* qbar, const float* kbar, const float* vbar, const void* kp, const void* vp,
+                     svgear_dtype dt, const int32_t* q_offsets, const int32_t* k_offsets, int B, int H, int64_t Nq,
+                     int64_t Nk, int d, int Cq, int Ck, int64_t budget_cost, float top_p, float scale, unsigned flags,
+                     float* scores, uint32_t* mask_bits, int32_t* row_ptr, int32_t* col_idx, int64_t* routed_cost,
+                     int64_t* row_budget, void* ws, size_t ws_bytes, void* stream) {
   const bool given = flags & SVGEAR_USE_GIVEN_SCORES;
+  const bool adaptive = top_p >= 0.f;
   if (!q_offsets || !k_offsets || !scores || !mask_bits || !row_ptr || !col_idx || !routed_cost || B <= 0 ||
       H <= 0 || Nq <= 0 || Nk <= 0 || Cq <= 0 || Ck <= 0 || Cq > 8192 || Ck > 8192 || budget_cost < 0 ||
       Nq > INT32_MAX / 2 || Nk > INT32_MAX / 2 || (flags & ~7u) || (int64_t)(Cq + 1) * (Ck + 1) > INT32_MAX / 2)
     return SVGEAR_ERR_INVALID;
+  if (adaptive && (!row_budget || !(top_p > 0.f && top_p <= 1.f))) return SVGEAR_ERR_INVALID;
+  if (!given || adaptive) {
+    if (!qbar || !kbar || (d != 64 && d != 128) || reinterpret_cast<uintptr_t>(qbar) % 16 ||
+        reinterpret_cast<uintptr_t>(kbar) % 16)
+      return SVGEAR_ERR_INVALID;
+  }
   if (!given) {
-    if (!qbar || !kbar || !vbar || !kp || !vp || (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) ||
-        reinterpret_cast<uintptr_t>(kp) % 16 || reinterpret_cast<uintptr_t>(vp) % 16 ||
-        reinterpret_cast<uintptr_t>(qbar) % 16 || reinterpret_cast<uintptr_t>(kbar) % 16)
+    if (!vbar || !kp || !vp || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) || reinterpret_cast<uintptr_t>(kp) % 16 ||
+        reinterpret_cast<uintptr_t>(vp) % 16)
       return SVGEAR_ERR_INVALID;
   }
   if (!ws || ws_bytes < svgear_probe_route_workspace(B, H, Nk, d, Cq, Ck)) return SVGEAR_ERR_WORKSPACE;
@@ -214,13 +316,47 @@ extern "C" int svgear_probe_route(const float* qbar, const float* kbar, const fl
     int rc = run_probe(qbar, kbar, vbar, kp, vp, dt, k_offsets, BH, Nk, d, Cq, Ck, scale,
                        !(flags & SVGEAR_PROBE_PLAIN), scores, sbar, mrow, q3, nd, dd, s);
     if (rc != SVGEAR_OK) return rc;
+  } else if (adaptive) {
+    int rc = run_sbar(qbar, kbar, k_offsets, BH, d, Cq, Ck, scale, sbar, mrow, s);
+    if (rc != SVGEAR_OK) return rc;
   }
-  const int per_row = (flags & SVGEAR_ROUTE_PER_ROW) ? 1 : 0;
+  const int per_row = (adaptive || (flags & SVGEAR_ROUTE_PER_ROW)) ? 1 : 0;
+  if (adaptive) {
+    top_p_budget_kernel<<<dim3(Cq, BH), kTopPThreads, (size_t)Ck * sizeof(unsigned long long), s>>>(
+        sbar, mrow, q_offsets, k_offsets, Cq, Ck, top_p, row_budget);
+    SVGEAR_LAUNCH_CHECK();
+  }
   select_kernel<<<dim3(per_row ? Cq : 1, BH), kSelThreads, 0, s>>>(scores, q_offsets, k_offsets, Cq, Ck, budget_cost,
-                                                                  per_row, kstar);
+                                                                  per_row, adaptive ? row_budget : nullptr, kstar);
   SVGEAR_LAUNCH_CHECK();
   build_kernel<<<BH, 256, (Cq + 2) * sizeof(int32_t), s>>>(scores, q_offsets, k_offsets, Cq, Ck, per_row, kstar,
                                                           mask_bits, row_ptr, col_idx, routed_cost);
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;
+}
+
+}  // namespace
+
+extern "C" int svgear_probe_route(const float* qbar, const float* kbar, const float* vbar, const void* kp,
+                                  const void* vp, svgear_dtype dt, const int32_t* q_offsets,
+                                  const int32_t* k_offsets, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
+                                  int Ck, int64_t budget_cost, float scale, unsigned flags, float* scores,
+                                  uint32_t* mask_bits, int32_t* row_ptr, int32_t* col_idx, int64_t* routed_cost,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  return probe_route_impl(qbar, kbar, vbar, kp, vp, dt, q_offsets, k_offsets, B, H, Nq, Nk, d, Cq, Ck, budget_cost,
+                          -1.f, scale, flags, scores, mask_bits, row_ptr, col_idx, routed_cost, nullptr, ws, ws_bytes,
+                          stream);
+}
+
+extern "C" int svgear_probe_route_top_p(const float* qbar, const float* kbar, const float* vbar, const void* kp,
+                                        const void* vp, svgear_dtype dt, const int32_t* q_offsets,
+                                        const int32_t* k_offsets, int B, int H, int64_t Nq, int64_t Nk, int d,
+                                        int Cq, int Ck, float top_p, float scale, unsigned flags, float* scores,
+                                        uint32_t* mask_bits, int32_t* row_ptr, int32_t* col_idx,
+                                        int64_t* routed_cost, int64_t* row_budget, void* ws, size_t ws_bytes,
+                                        void* stream) {
+  if (!(top_p > 0.f && top_p <= 1.f) || (flags & SVGEAR_ROUTE_PER_ROW)) return SVGEAR_ERR_INVALID;
+  return probe_route_impl(qbar, kbar, vbar, kp, vp, dt, q_offsets, k_offsets, B, H, Nq, Nk, d, Cq, Ck, 0, top_p,
+                          scale, flags, scores, mask_bits, row_ptr, col_idx, routed_cost, row_budget, ws, ws_bytes,
+                          stream);
 }

@@ -187,3 +187,41 @@ def test_attention_is_deterministic():
         outs.append((O.clone(), r["lab_k"].clone(), r["mask_bits"].clone(), ck.clone()))
     for x, y in zip(*outs):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("name", ["mini_video", "mini_video_tail", "mini_manyk"])
+def test_end_to_end_chain_with_adaptive_row_budgets_matches_oracle(name):
+    """The whole path with the per-query-cluster adaptive budgets (the top-p reading) in place of
+    one budget per head: budgets valid against the oracle's, mask an exact function of the GPU's
+    scores and budgets, output within tolerance of Eq. (1) + Eq. (6) on that mask."""
+    wl = get_workload(name)
+    p = 0.85
+    Q, K, V = make_qkv(wl, dev())
+    B, H = Q.shape[:2]
+    cq = init_centroids(Q, wl.Cq, wl.seed, 0, wl.n_tail)
+    ck = init_centroids(K, wl.Ck, wl.seed, 1, wl.n_tail)
+    O, r = sv.attention_layer(Q, K, V, cq, ck, wl.iters, 0, wl.n_tail, top_p=p)
+    torch.cuda.synchronize()
+    scale = orc.scale_of(wl.d)
+    from helpers import bits_to_mask
+    for b in range(B):
+        for h in range(H):
+            qcnt, kcnt = to_np(r["qcnt"][b, h]), to_np(r["kcnt"][b, h])
+            got = to_np(r["row_budget"][b, h])
+            args = (to_np(r["qbar"][b, h]), to_np(r["kbar"][b, h]), qcnt, kcnt)
+            lo = orc.top_p_row_budgets(*args, p * (1 - 1e-4), scale)[0]
+            hi = orc.top_p_row_budgets(*args, p * (1 + 1e-4), scale)[0]
+            mid = orc.top_p_row_budgets(*args, p, scale)[0]
+            assert np.all(lo <= got) and np.all(got <= hi)
+            assert np.array_equal(got[lo == hi], mid[lo == hi])
+            m_ref = orc.route(to_np(r["scores"][b, h]), qcnt, kcnt, 0, n_tail_q=wl.n_tail, n_tail_k=wl.n_tail,
+                              row_budgets=got)[0]
+            m = bits_to_mask(to_np(r["mask_bits"][b, h]), wl.Ck)
+            assert np.array_equal(m, full_mask(m_ref, wl.Cq, wl.Ck))
+            lq = np.repeat(np.arange(wl.Cq + 1), np.diff(to_np(r["qoff"][b, h])))
+            lk = np.repeat(np.arange(wl.Ck + 1), np.diff(to_np(r["koff"][b, h])))
+            kb = np.concatenate([to_np(r["kbar"][b, h]), np.zeros((1, wl.d), np.float32)])
+            vb = np.concatenate([to_np(r["vbar"][b, h]), np.zeros((1, wl.d), np.float32)])
+            op_ref = orc.attention_comp(to_np(r["Qp"][b, h]), to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
+                                        vb, m, scale)
+            assert rel_l2(to_np(O[b, h]), orc.unpermute_rows(op_ref, to_np(r["perm_q"][b, h]))) <= TOL[wl.dtype]

@@ -14,26 +14,30 @@ from helpers import dev, to_np, init_centroids, bits_to_mask, full_mask, rel_l2
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(name, iters):
+def _run_full(name, iters, top_p=None):
     wl = get_workload(name)
     Q, K, V = make_qkv(wl, dev())
     cq0 = init_centroids(Q, wl.Cq, wl.seed, 0, wl.n_tail)
     ck0 = init_centroids(K, wl.Ck, wl.seed, 1, wl.n_tail)
     cq, ck = cq0.clone(), ck0.clone()
     budget = budget_pairs(wl.rho, wl.N, wl.N)
-    O, r = sv.attention_layer(Q, K, V, cq, ck, iters, budget, wl.n_tail)
+    O, r = sv.attention_layer(Q, K, V, cq, ck, iters, budget, wl.n_tail, top_p=top_p)
     torch.cuda.synchronize()
     return wl, Q, K, V, cq0, ck0, O, r, budget
 
 
-@pytest.mark.parametrize("name", ["wan", "hunyuan", "wan_c300"])
-def test_full_size_layer_sampled_parity(name):
+@pytest.mark.parametrize("name,top_p", [("wan", None), ("hunyuan", None), ("wan_c300", None), ("wan_c300", 0.85)])
+def test_full_size_layer_sampled_parity(name, top_p):
+    """top_p = None: one budget per head; 0.85 with 300/1000 clusters: the adaptive
+    per-query-cluster budgets at the cluster counts and TopP of the paper's Wan2.2 row
+    (hyper-parameter table)."""
     iters = 2  # the clustering only has to be plausible here; lock-step parity is checked below
-    wl, Q, K, V, cq0, ck0, O, r, budget = _run_full(name, iters)
+    wl, Q, K, V, cq0, ck0, O, r, budget = _run_full(name, iters, top_p)
     nv = wl.N - wl.n_tail
     rng = np.random.default_rng(1)
     scale = orc.scale_of(wl.d)
-    assert int(r["routed_cost"].max()) <= budget
+    if top_p is None:
+        assert int(r["routed_cost"].max()) <= budget
     for h in sorted({0, wl.H - 1}):
         qoff, koff = to_np(r["qoff"][0, h]), to_np(r["koff"][0, h])
         lab_q, lab_k = to_np(r["lab_q"][0, h]), to_np(r["lab_k"][0, h])
@@ -72,8 +76,18 @@ def test_full_size_layer_sampled_parity(name):
             ref = (diff * diff).sum((1, 2)) / sizes[b]
             assert np.all(np.abs(got[:, b] - ref) <= 1e-3 * np.abs(ref) + 1e-6 * row_max)
         # --- routing: bit-exact function of the scores the GPU produced
+        row_budgets = None
+        if top_p is not None:
+            # the prefix length is decided in fp32 on the GPU: exact wherever the oracle's answer is
+            # the same for p within 1e-4, between those answers elsewhere
+            row_budgets = to_np(r["row_budget"][0, h])
+            args = (qbar, kbar, np.diff(qoff[: wl.Cq + 1]), sizes)
+            lo, mid, hi = (orc.top_p_row_budgets(*args, top_p * f, scale)[0] for f in (1 - 1e-4, 1.0, 1 + 1e-4))
+            assert np.all(lo <= row_budgets) and np.all(row_budgets <= hi)
+            assert np.array_equal(row_budgets[lo == hi], mid[lo == hi])
+            assert (row_budgets != mid).sum() <= wl.Cq // 50
         m_ref, rp_ref, ci_ref, cost_ref = orc.route(got, np.diff(qoff[: wl.Cq + 1]), sizes, budget,
-                                                    n_tail_q=wl.n_tail, n_tail_k=wl.n_tail)
+                                                    n_tail_q=wl.n_tail, n_tail_k=wl.n_tail, row_budgets=row_budgets)
         mask = bits_to_mask(to_np(r["mask_bits"][0, h]), wl.Ck)
         assert np.array_equal(mask, full_mask(m_ref, wl.Cq, wl.Ck))
         assert int(r["routed_cost"][0, h]) == cost_ref

@@ -101,3 +101,76 @@ def test_route_is_deterministic():
     torch.cuda.synchronize()
     for k in ("scores", "mask_bits", "row_ptr", "routed_cost"):
         assert torch.equal(a[k], b[k])
+
+
+# ---------------------------------------------------- adaptive (top-p reading) row budgets
+
+
+def _check_row_budgets(got, ref_head, wl, p, scale):
+    """The prefix length is an integer decided by floating point (fp32 masses on the GPU, fp64
+    in the oracle): a row's budget must equal the oracle's wherever the oracle's own answer
+    does not change for p within 1e-4 of the given one, and lie between those two answers
+    elsewhere. Returns the number of rows that differ from the oracle's answer at p."""
+    args = (ref_head["qbar"], ref_head["kbar"], ref_head["qcnt"], ref_head["kcnt"])
+    mid = orc.top_p_row_budgets(*args, p, scale)[0]
+    lo = orc.top_p_row_budgets(*args, p * (1 - 1e-4), scale)[0]
+    hi = orc.top_p_row_budgets(*args, min(p * (1 + 1e-4), 1.0), scale)[0]
+    assert np.all(lo <= got) and np.all(got <= hi), (got, lo, hi)
+    settled = lo == hi
+    assert np.array_equal(got[settled], mid[settled])
+    return int((got != mid).sum())
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_manyk"])
+@pytest.mark.parametrize("p", [0.3, 0.85, 1.0])
+def test_top_p_row_budgets_and_routing_match_oracle(name, p):
+    wl, refs, qbar, kbar, vbar, Kp, Vp, qoff, koff = _stage_inputs(name)
+    B, H = qbar.shape[:2]
+    scale = orc.scale_of(wl.d)
+    inj = torch.stack([torch.stack([torch.from_numpy(refs[b][h]["scores"].astype(np.float32)) for h in range(H)])
+                       for b in range(B)]).to(dev())
+    r = sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, flags=sv.USE_GIVEN_SCORES, scores=inj.clone(),
+                       top_p=p)
+    torch.cuda.synchronize()
+    differing = 0
+    for b in range(B):
+        for h in range(H):
+            ref = refs[b][h]
+            got = to_np(r["row_budget"][b, h])
+            differing += _check_row_budgets(got, ref, wl, p, scale)
+            # routing is an exact function of the scores and the row budgets
+            m_ref, rp_ref, ci_ref, cost_ref = orc.route(to_np(inj[b, h]), ref["qcnt"], ref["kcnt"], 0,
+                                                        n_tail_q=wl.n_tail, n_tail_k=wl.n_tail, row_budgets=got)
+            fm = full_mask(m_ref, wl.Cq, wl.Ck)
+            assert np.array_equal(bits_to_mask(to_np(r["mask_bits"][b, h]), wl.Ck), fm)
+            assert int(r["routed_cost"][b, h]) == cost_ref
+            rp, ci = to_np(r["row_ptr"][b, h]), to_np(r["col_idx"][b, h])
+            for a in range(wl.Cq + 1):
+                assert ci[rp[a]: rp[a + 1]].tolist() == np.nonzero(fm[a])[0].tolist()
+    assert differing <= max(1, B * H * wl.Cq // 50)
+
+
+def test_top_p_with_probe_equals_top_p_with_its_own_scores_given():
+    # the probe leg and the given-scores leg (which computes the centroid logits alone) agree
+    wl, refs, qbar, kbar, vbar, Kp, Vp, qoff, koff = _stage_inputs("mini_video_tail")
+    scale = orc.scale_of(wl.d)
+    a = sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, top_p=0.8)
+    b = sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, flags=sv.USE_GIVEN_SCORES,
+                       scores=a["scores"].clone(), top_p=0.8)
+    torch.cuda.synchronize()
+    for k in ("row_budget", "mask_bits", "row_ptr", "routed_cost"):
+        assert torch.equal(a[k], b[k])
+    # and the global-budget entry point is untouched by the adaptive one
+    c = sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, budget_pairs(0.25, wl.N, wl.N), scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a["scores"], c["scores"])
+
+
+def test_top_p_argument_checks():
+    wl, refs, qbar, kbar, vbar, Kp, Vp, qoff, koff = _stage_inputs("tiny")
+    scale = orc.scale_of(wl.d)
+    for bad in (0.0, -0.5, 1.5, float("nan")):
+        with pytest.raises(RuntimeError):
+            sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, top_p=bad)
+    with pytest.raises(RuntimeError):
+        sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, flags=sv.ROUTE_PER_ROW, top_p=0.5)
