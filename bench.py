@@ -49,6 +49,9 @@ def parse():
                     help="layer: one JSON line for the whole hot path (default); sweep: routed-budget sweep with "
                          "per-stage times and the compensation-only / dense brackets; trajectory: warm-started "
                          "k-means over denoising steps")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="profiling aid: run the Q and the K/V call of a stage one after the other on one stream, so "
+                         "that a kernel trace shows each kernel's duration when it has the GPU to itself")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE run can be scaled against it")
@@ -84,18 +87,22 @@ class StageTimer:
         return out
 
 
+ONE_STREAM = False
+
+
 def run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget, timer=None):
     """One pass of the whole path (cold k-means start: centroids reset from the seeded init)."""
+    pair = (lambda f, g: (f(), g())) if ONE_STREAM else sv.run_pair
     cq.copy_(cq0)
     ck.copy_(ck0)
     scale = float(wl.d) ** -0.5
     if timer: timer.mark("start")
     # the Q call and the K/V call of a stage are independent: they run side by side on two
     # streams and are joined before the stage's mark (as attention_layer does)
-    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = sv.run_pair(lambda: sv.kmeans(Q, cq, wl.iters, wl.n_tail),
-                                                        lambda: sv.kmeans(K, ck, wl.iters, wl.n_tail, x2=V))
+    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = pair(lambda: sv.kmeans(Q, cq, wl.iters, wl.n_tail),
+                                                 lambda: sv.kmeans(K, ck, wl.iters, wl.n_tail, x2=V))
     if timer: timer.mark("kmeans")
-    (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = sv.run_pair(
+    (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = pair(
         lambda: sv.permute(lab_q, wl.Cq, [Q], wl.n_tail), lambda: sv.permute(lab_k, wl.Ck, [K, V], wl.n_tail))
     if timer: timer.mark("permute")
     r = sv.probe_route(cq, ck, vbar, Kp, Vp, qoff, koff, budget, scale)
@@ -312,7 +319,9 @@ def run_trajectory(sv, args, wl):
 
 
 def main():
+    global ONE_STREAM
     args = parse()
+    ONE_STREAM = args.one_stream
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (heads are independent and would shard over GPUs with no "
               "communication inside the layer, but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)

@@ -266,23 +266,39 @@ constexpr int kFilterRowsPerWave = 64;  // two 32-row operand sets share every c
 constexpr int kFilterRows = kFilterWaves * kFilterRowsPerWave;
 
 // |x|_2 of every row (fp32), once per call: the input does not change between iterations.
+// D/8 lanes share a row (16 bytes each, so a wave's load covers whole rows back to back), four
+// rows per lane group in flight.
+constexpr int kNormPasses = 4;
 template <int D>
 __global__ void __launch_bounds__(256)
 row_norm_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, float* __restrict__ xnorm) {
-  const int bh = blockIdx.y;
-  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (row >= nv) return;
-  const bf16_t* xr = x + head_base(st, bh, H) + row * st.n;
-  float acc = 0.f;
+  constexpr int LPR = D / 8;      // lanes per row
+  constexpr int RPP = 256 / LPR;  // rows per pass of the workgroup
+  const int bh = blockIdx.y, sub = threadIdx.x / LPR, lane = threadIdx.x % LPR;
+  const int64_t row0 = (int64_t)blockIdx.x * (RPP * kNormPasses) + sub;
+  const bf16_t* xb = x + head_base(st, bh, H) + lane * 8;
+  uint4 raw[kNormPasses];
 #pragma unroll
-  for (int t = 0; t < D; t += 4) {
-    const float4 v = load4(xr + t);
-    acc = __builtin_fmaf(v.x, v.x, acc);
-    acc = __builtin_fmaf(v.y, v.y, acc);
-    acc = __builtin_fmaf(v.z, v.z, acc);
-    acc = __builtin_fmaf(v.w, v.w, acc);
+  for (int p = 0; p < kNormPasses; ++p) {
+    const int64_t row = row0 + p * RPP;
+    raw[p] = row < nv ? *reinterpret_cast<const uint4*>(xb + row * st.n) : uint4{0u, 0u, 0u, 0u};
   }
-  xnorm[(int64_t)bh * nv + row] = sqrtf(acc) * 1.00002f;  // upper bound (the fp32 sum is within d 2^-24)
+#pragma unroll
+  for (int p = 0; p < kNormPasses; ++p) {
+    const uint32_t w[4] = {raw[p].x, raw[p].y, raw[p].z, raw[p].w};
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+      acc = __builtin_fmaf(lo, lo, acc);
+      acc = __builtin_fmaf(hi, hi, acc);
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    const int64_t row = row0 + p * RPP;
+    // upper bound (an fp32 sum of d squares, in any order, is within d 2^-24 of the exact one)
+    if (lane == 0 && row < nv) xnorm[(int64_t)bh * nv + row] = sqrtf(acc) * 1.00002f;
+  }
 }
 
 // How far every centroid moved since the previous call, |c - c_prev| rounded up, and
@@ -760,7 +776,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   if constexpr (kFilter) {
     SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
-    row_norm_kernel<D><<<dim3((unsigned)ceil_div(nv, 256), BH), 256, 0, s>>>(
+    row_norm_kernel<D><<<dim3((unsigned)ceil_div(nv, (256 / (D / 8)) * kNormPasses), BH), 256, 0, s>>>(
         reinterpret_cast<const bf16_t*>(x), st, H, nv, xnorm);
     SVGEAR_LAUNCH_CHECK();
   }

@@ -203,27 +203,37 @@ value_stats_kernel(const float* __restrict__ vbar, const bf16_t* __restrict__ vp
 #pragma unroll
   for (int k = 0; k < 8; ++k) vbl[k] = vb[k];
   const bf16_t* vh = vp + (int64_t)bh * Nk * D + lane * 8;
-  for (int j = start + slot; j < end; j += SLOTS) {
-    const uint4 raw = *reinterpret_cast<const uint4*>(vh + (int64_t)j * D);
-    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-    float p_nd = 0.f, p_dd = 0.f;
+  constexpr int INFLIGHT = 4;  // independent key fetches per lane group
+  for (int j0 = start + slot; j0 < end; j0 += INFLIGHT * SLOTS) {
+    uint4 raw[INFLIGHT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float d0 = __uint_as_float(w[i] << 16) - vbl[2 * i];
-      const float d1 = __uint_as_float(w[i] & 0xffff0000u) - vbl[2 * i + 1];
-      p_nd = __builtin_fmaf(d0, d0, p_nd);
-      p_dd = __builtin_fmaf(d0, vbl[2 * i], p_dd);
-      p_nd = __builtin_fmaf(d1, d1, p_nd);
-      p_dd = __builtin_fmaf(d1, vbl[2 * i + 1], p_dd);
+    for (int u = 0; u < INFLIGHT; ++u) {
+      const int j = j0 + u * SLOTS;
+      raw[u] = j < end ? *reinterpret_cast<const uint4*>(vh + (int64_t)j * D) : uint4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
-    for (int o = LPK / 2; o > 0; o >>= 1) {
-      p_nd += __shfl_xor(p_nd, o);
-      p_dd += __shfl_xor(p_dd, o);
-    }
-    if (lane == 0) {
-      nd[(int64_t)bh * stat_stride + j] = p_nd;
-      dd[(int64_t)bh * stat_stride + j] = p_dd;
+    for (int u = 0; u < INFLIGHT; ++u) {
+      const int j = j0 + u * SLOTS;
+      const uint32_t w[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+      float p_nd = 0.f, p_dd = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float d0 = __uint_as_float(w[i] << 16) - vbl[2 * i];
+        const float d1 = __uint_as_float(w[i] & 0xffff0000u) - vbl[2 * i + 1];
+        p_nd = __builtin_fmaf(d0, d0, p_nd);
+        p_dd = __builtin_fmaf(d0, vbl[2 * i], p_dd);
+        p_nd = __builtin_fmaf(d1, d1, p_nd);
+        p_dd = __builtin_fmaf(d1, vbl[2 * i + 1], p_dd);
+      }
+#pragma unroll
+      for (int o = LPK / 2; o > 0; o >>= 1) {
+        p_nd += __shfl_xor(p_nd, o);
+        p_dd += __shfl_xor(p_dd, o);
+      }
+      if (lane == 0 && j < end) {
+        nd[(int64_t)bh * stat_stride + j] = p_nd;
+        dd[(int64_t)bh * stat_stride + j] = p_dd;
+      }
     }
   }
 }
