@@ -43,56 +43,99 @@ struct CutState {
   unsigned long long hist[256];
   unsigned long long prefix;
   long long remaining;
-  int done;
+  long long wave_total[4];
+  unsigned int count[256];  // items per digit
+  int crossed[2];           // per pass parity: some digit's cumulative weight exceeded what is left
+  int single;               // the digit that crossed holds one item: that item is the cut
 };
 
 // Walks n_items items in descending key order (keys unique) and returns the key of the first
 // one whose inclusive cumulative weight exceeds rem, or 0 if every item fits. visit(it, key,
-// weight) returns false for items that do not take part. Called by all threads of the block.
+// weight) returns false for items that do not take part. Called by all threads of the block
+// (THREADS >= 256, a multiple of 64).
+// Items are visited four at a time per thread, all their loads issued before the first
+// histogram update; the digit of the cut is found by a 256-wide scan of the histogram from
+// the top digit down (four waves, shuffles), not by one thread walking it. As soon as the
+// digit that crosses holds a single item, that item is the cut and one more walk fetches its
+// key (scores are mostly distinct, so this happens after three or four of the eight digits).
 template <int THREADS, class Visit>
-__device__ __forceinline__ unsigned long long radix_cut(CutState& st, long long rem, int64_t n_items, Visit visit) {
+__device__ __forceinline__ unsigned long long radix_cut(CutState& st, long long rem, int n_items, Visit visit) {
+  constexpr int U = 4;
+  static_assert(THREADS >= 256 && THREADS % 64 == 0, "the histogram scan uses the first four waves");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x == 0) {
     st.remaining = rem > 0 ? rem : 0;
     st.prefix = 0ull;
-    st.done = 0;
   }
   for (int pass = 0; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
-    for (int i = threadIdx.x; i < 256; i += THREADS) st.hist[i] = 0ull;
-    __syncthreads();
-    if (st.done) break;
-    const unsigned long long prefix = st.prefix;
-    for (int64_t it = threadIdx.x; it < n_items; it += THREADS) {
-      uint64_t key;
-      unsigned long long weight;
-      if (!visit(it, key, weight)) continue;
-      if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
-      atomicAdd(&st.hist[(key >> shift) & 255u], weight);
+    for (int i = threadIdx.x; i < 256; i += THREADS) {
+      st.hist[i] = 0ull;
+      st.count[i] = 0u;
     }
-    __syncthreads();
     if (threadIdx.x == 0) {
-      long long cum = 0;
-      const long long left = st.remaining;
-      int found = -1;
-      for (int dg = 255; dg >= 0; --dg) {
-        const long long h = (long long)st.hist[dg];
-        if (cum + h > left) {
-          found = dg;
-          break;
-        }
-        cum += h;
+      st.crossed[pass & 1] = 0;
+      st.single = 0;
+    }
+    __syncthreads();
+    const unsigned long long prefix = st.prefix;
+    const long long left = st.remaining;
+    for (int base = 0; base < n_items; base += U * THREADS) {  // same trip count for every thread
+      uint64_t key[U];
+      unsigned long long weight[U];
+      bool on[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int it = base + u * THREADS + (int)threadIdx.x;
+        on[u] = it < n_items && visit(it, key[u], weight[u]);
+        on[u] = on[u] && (pass == 0 || (key[u] >> (shift + 8)) == prefix);
       }
-      if (found < 0) {  // everything fits (can only happen on the first pass)
-        st.done = 1;
-        st.prefix = 0ull;
-      } else {
-        st.remaining = left - cum;
-        st.prefix = (prefix << 8) | (unsigned long long)found;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (!on[u]) continue;
+        const int digit = (int)((key[u] >> shift) & 255u);
+        atomicAdd(&st.hist[digit], weight[u]);
+        atomicAdd(&st.count[digit], 1u);
       }
     }
     __syncthreads();
+    // thread i < 256 owns digit 255 - i: inclusive sums in descending digit order
+    long long h = 0, incl = 0;
+    if (threadIdx.x < 256) {
+      h = (long long)st.hist[255 - threadIdx.x];
+      incl = h;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const long long t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+      }
+      if (lane == 63) st.wave_total[wave] = incl;
+    }
+    __syncthreads();
+    if (threadIdx.x < 256) {
+      for (int w = 0; w < wave; ++w) incl += st.wave_total[w];
+      if (incl > left && incl - h <= left) {  // the first digit that does not fit: one thread at most
+        st.remaining = left - (incl - h);
+        st.prefix = (prefix << 8) | (unsigned long long)(255 - threadIdx.x);
+        st.crossed[pass & 1] = 1;
+        st.single = st.count[255 - threadIdx.x] == 1u;
+      }
+    }
+    __syncthreads();
+    if (!st.crossed[pass & 1]) return 0ull;  // everything fits (can only happen on the first pass)
+    if (st.single && pass < 7) {
+      const unsigned long long found = st.prefix;  // the leading 8 (pass + 1) bits of the cut
+      __syncthreads();
+      for (int base = 0; base < n_items; base += THREADS) {
+        const int it = base + (int)threadIdx.x;
+        uint64_t key;
+        unsigned long long weight;
+        if (it < n_items && visit(it, key, weight) && (key >> shift) == found) st.prefix = key;
+      }
+      __syncthreads();
+      return st.prefix;
+    }
   }
-  __syncthreads();
   return st.prefix;
 }
 
@@ -110,7 +153,7 @@ select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_of
   const int64_t Nq = qo[Cq + 1], Nk = ko[Ck + 1];
   const int64_t tq = qo[Cq + 1] - qo[Cq], tk = ko[Ck + 1] - ko[Ck];
   const int a_lo = per_row ? seg : 0, a_hi = per_row ? seg + 1 : Cq;
-  const int64_t n_items = (int64_t)(a_hi - a_lo) * Ck;
+  const int n_items = (a_hi - a_lo) * Ck;  // (Cq + 1)(Ck + 1) fits 31 bits (checked by the caller)
   long long rem;
   if (row_budget) {
     rem = row_budget[(int64_t)bh * Cq + seg];
@@ -120,9 +163,10 @@ select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_of
   } else {
     rem = budget - (tq * Nk + (Nq - tq) * tk);
   }
-  const unsigned long long cut = radix_cut<kSelThreads>(st, rem, n_items, [&](int64_t it, uint64_t& key,
+  const unsigned long long cut = radix_cut<kSelThreads>(st, rem, n_items, [&](int it, uint64_t& key,
                                                                               unsigned long long& weight) {
-    const int a = a_lo + (int)(it / Ck), b = (int)(it % Ck);
+    const int ar = (int)((unsigned)it / (unsigned)Ck);
+    const int a = a_lo + ar, b = it - ar * Ck;
     const int64_t cost = (int64_t)(qo[a + 1] - qo[a]) * (int64_t)(ko[b + 1] - ko[b]);
     if (cost <= 0) return false;
     key = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b));
@@ -176,9 +220,9 @@ top_p_budget_kernel(const float* __restrict__ sbar, const float* __restrict__ mr
   const double want = ceil((double)top_p * (double)total);
   const long long need = want >= 1.0 ? (long long)want : 1ll;
   auto key_of = [&](int b) { return (wgt[b] << kTopPIndexBits) | (unsigned long long)((1 << kTopPIndexBits) - 1 - b); };
-  const unsigned long long cut = radix_cut<kTopPThreads>(st, need - 1, Ck, [&](int64_t it, uint64_t& key,
+  const unsigned long long cut = radix_cut<kTopPThreads>(st, need - 1, Ck, [&](int it, uint64_t& key,
                                                                                unsigned long long& weight) {
-    const int b = (int)it;
+    const int b = it;
     if (ko[b + 1] <= ko[b]) return false;
     key = key_of(b);
     weight = wgt[b];
@@ -194,47 +238,56 @@ top_p_budget_kernel(const float* __restrict__ sbar, const float* __restrict__ mr
   if (threadIdx.x == 0) row_budget[(int64_t)bh * Cq + a] = qa * (int64_t)sh_keys;
 }
 
-// grid (BH). Builds the bit mask, the CSR lists and the routed cost from K*.
-__global__ void __launch_bounds__(256)
+constexpr int kBuildThreads = 1024;
+
+// grid (BH). Builds the bit mask, the CSR lists and the routed cost from K*. A wave takes a
+// row of blocks at a time, 64 consecutive key clusters per step (coalesced score loads), and
+// forms two mask words with one ballot.
+__global__ void __launch_bounds__(kBuildThreads)
 build_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_offsets,
              const int32_t* __restrict__ k_offsets, int Cq, int Ck, int per_row,
              const uint64_t* __restrict__ kstar, uint32_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
              int32_t* __restrict__ col_idx, int64_t* __restrict__ routed_cost) {
   extern __shared__ int32_t rowcnt[];  // Cq+2
   __shared__ unsigned long long cost_sum;
-  const int bh = blockIdx.x;
+  const int bh = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int NWAVES = kBuildThreads / 64;
   const int R = Cq + 1, Cc = Ck + 1, W = (Cc + 31) / 32;
   const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
   const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
   const float* sc = scores + (int64_t)bh * Cq * Ck;
   uint32_t* mb = mask_bits + (int64_t)bh * R * W;
-  for (int a = threadIdx.x; a < R + 1; a += 256) rowcnt[a] = 0;
   if (threadIdx.x == 0) cost_sum = 0ull;
   __syncthreads();
   long long my_cost = 0;
-  for (int it = threadIdx.x; it < R * W; it += 256) {
-    const int a = it / W, w = it % W;
+  for (int a = wave; a < R; a += NWAVES) {
     const int64_t qa = qo[a + 1] - qo[a];
-    uint32_t bits = 0;
-    if (qa > 0) {
-      const uint64_t ks = (a < Cq) ? kstar[(int64_t)bh * (per_row ? Cq : 1) + (per_row ? a : 0)] : 0ull;
-      for (int j = 0; j < 32; ++j) {
-        const int b = w * 32 + j;
-        if (b >= Cc) break;
+    const uint64_t ks = (a < Cq) ? kstar[(int64_t)bh * (per_row ? Cq : 1) + (per_row ? a : 0)] : 0ull;
+    int cnt = 0;
+    for (int b0 = 0; b0 < W * 32; b0 += 64) {
+      const int b = b0 + lane;
+      bool on = false;
+      if (qa > 0 && b < Cc) {
         const int64_t kb = ko[b + 1] - ko[b];
-        if (kb <= 0) continue;
-        bool on = (a == Cq) || (b == Ck);
-        if (!on) on = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b)) > ks;
-        if (on) {
-          bits |= 1u << j;
-          my_cost += qa * kb;
+        if (kb > 0) {
+          on = (a == Cq) || (b == Ck);
+          if (!on) on = block_key(sc[(int64_t)a * Ck + b], (uint32_t)(a * Ck + b)) > ks;
+          if (on) my_cost += qa * kb;
         }
       }
+      const unsigned long long bits = __ballot(on);
+      cnt += __popcll(bits);
+      if (lane == 0) {
+        mb[a * W + (b0 >> 5)] = (uint32_t)bits;
+        if ((b0 >> 5) + 1 < W) mb[a * W + (b0 >> 5) + 1] = (uint32_t)(bits >> 32);
+      }
     }
-    mb[it] = bits;
-    if (bits) atomicAdd(&rowcnt[a], __popc(bits));
+    if (lane == 0) rowcnt[a] = cnt;
   }
-  atomicAdd(&cost_sum, (unsigned long long)my_cost);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) my_cost += __shfl_xor(my_cost, o);
+  if (lane == 0 && my_cost) atomicAdd(&cost_sum, (unsigned long long)my_cost);
+  __threadfence_block();
   __syncthreads();
   int32_t* rp = row_ptr + (int64_t)bh * (R + 1);
   if (threadIdx.x == 0) {
@@ -249,16 +302,15 @@ build_kernel(const float* __restrict__ scores, const int32_t* __restrict__ q_off
     routed_cost[bh] = (int64_t)cost_sum;
   }
   __syncthreads();
+  // routed key clusters of every row, ascending: a wave per row, a lane per set bit
   int32_t* ci = col_idx + (int64_t)bh * R * Cc;
-  for (int a = threadIdx.x; a < R; a += 256) {
+  for (int a = wave; a < R; a += NWAVES) {
     int32_t pos = rowcnt[a];
-    for (int w = 0; w < W; ++w) {
-      uint32_t bits = mb[a * W + w];
-      while (bits) {
-        const int j = __ffs(bits) - 1;
-        bits &= bits - 1;
-        ci[pos++] = w * 32 + j;
-      }
+    for (int w0 = 0; w0 < W; w0 += 2) {
+      unsigned long long bits = mb[a * W + w0];
+      if (w0 + 1 < W) bits |= (unsigned long long)mb[a * W + w0 + 1] << 32;
+      if ((bits >> lane) & 1ull) ci[pos + __popcll(bits & ((1ull << lane) - 1ull))] = w0 * 32 + lane;
+      pos += __popcll(bits);
     }
   }
 }
@@ -329,7 +381,7 @@ int probe_route_impl(const float* qbar, const float* kbar, const float* vbar, co
   select_kernel<<<dim3(per_row ? Cq : 1, BH), kSelThreads, 0, s>>>(scores, q_offsets, k_offsets, Cq, Ck, budget_cost,
                                                                   per_row, adaptive ? row_budget : nullptr, kstar);
   SVGEAR_LAUNCH_CHECK();
-  build_kernel<<<BH, 256, (Cq + 2) * sizeof(int32_t), s>>>(scores, q_offsets, k_offsets, Cq, Ck, per_row, kstar,
+  build_kernel<<<BH, kBuildThreads, (Cq + 2) * sizeof(int32_t), s>>>(scores, q_offsets, k_offsets, Cq, Ck, per_row, kstar,
                                                           mask_bits, row_ptr, col_idx, routed_cost);
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;
