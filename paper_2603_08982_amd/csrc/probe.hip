@@ -24,56 +24,79 @@ constexpr float kMaxExponent = 40.0f;  // e^40 squared still fits fp32
 // pieces q = hi + mid + lo (exact: 3 x 8 significant bits), laid out as B operands of
 // v_mfma_f32_32x32x16_bf16: [a-block][piece][s][lane = a%32 + 32*((k%16)/8)][k%8], zero rows
 // for a >= Cq.
+constexpr int kSbarRows = 4;  // query centroids per workgroup: each kbar row fetched serves all of them
+
 template <int D>
 __global__ void __launch_bounds__(256)
 sbar_kernel(const float* __restrict__ qbar, const float* __restrict__ kbar, const int32_t* __restrict__ k_offsets,
             int Cq, int Ck, float scale, float* __restrict__ sbar, float* __restrict__ mrow,
             bf16_t* __restrict__ q3) {
-  __shared__ float q[D];
-  __shared__ float red[256];
-  const int a = blockIdx.x, bh = blockIdx.y;
-  const float* qa = qbar + ((int64_t)bh * Cq + (a < Cq ? a : 0)) * D;
-  for (int t = threadIdx.x; t < D; t += 256) q[t] = a < Cq ? qa[t] : 0.f;
-  __syncthreads();
-  if (q3 && threadIdx.x < D) {
-    constexpr int KSN = D / 16;
-    const int k = threadIdx.x, ab = a >> 5, nab = (Cq + 31) >> 5;
-    const float v = q[k];
-    const bf16_t hi = f32_to_bf16(v);
-    const float r1 = v - bf16_to_f32(hi);
-    const bf16_t mid = f32_to_bf16(r1);
-    const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
-    const int lane = (a & 31) + 32 * ((k & 15) >> 3);
-    bf16_t* dst = q3 + ((((int64_t)bh * nab + ab) * 3) * KSN + (k >> 4)) * 512 + lane * 8 + (k & 7);
-    dst[0] = hi;
-    dst[(int64_t)KSN * 512] = mid;
-    dst[(int64_t)2 * KSN * 512] = lo;
+  __shared__ float q[kSbarRows][D];
+  __shared__ float red[kSbarRows][4];
+  const int a0 = blockIdx.x * kSbarRows, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < kSbarRows * D; i += 256) {
+    const int a = a0 + i / D;
+    q[i / D][i % D] = a < Cq ? qbar[((int64_t)bh * Cq + a) * D + i % D] : 0.f;
   }
-  if (a >= Cq) return;
+  __syncthreads();
+  if (q3) {
+    constexpr int KSN = D / 16;
+    for (int i = threadIdx.x; i < kSbarRows * D; i += 256) {
+      const int a = a0 + i / D, k = i % D, ab = a >> 5, nab = (Cq + 31) >> 5;
+      const float v = q[i / D][k];
+      const bf16_t hi = f32_to_bf16(v);
+      const float r1 = v - bf16_to_f32(hi);
+      const bf16_t mid = f32_to_bf16(r1);
+      const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+      const int ln = (a & 31) + 32 * ((k & 15) >> 3);
+      bf16_t* dst = q3 + ((((int64_t)bh * nab + ab) * 3) * KSN + (k >> 4)) * 512 + ln * 8 + (k & 7);
+      dst[0] = hi;
+      dst[(int64_t)KSN * 512] = mid;
+      dst[(int64_t)2 * KSN * 512] = lo;
+    }
+  }
+  if (a0 >= Cq) return;
   const int32_t* off = k_offsets + (int64_t)bh * (Ck + 2);
-  float mx = -INFINITY;
+  float mx[kSbarRows];
+#pragma unroll
+  for (int r = 0; r < kSbarRows; ++r) mx[r] = -INFINITY;
   for (int b = threadIdx.x; b < Ck; b += 256) {
     const float4* kb = reinterpret_cast<const float4*>(kbar + ((int64_t)bh * Ck + b) * D);
-    float dot = 0.f;
+    float dot[kSbarRows];
+#pragma unroll
+    for (int r = 0; r < kSbarRows; ++r) dot[r] = 0.f;
 #pragma unroll 8
     for (int t = 0; t < D / 4; ++t) {
       const float4 v = kb[t];
-      dot = __builtin_fmaf(q[4 * t], v.x, dot);
-      dot = __builtin_fmaf(q[4 * t + 1], v.y, dot);
-      dot = __builtin_fmaf(q[4 * t + 2], v.z, dot);
-      dot = __builtin_fmaf(q[4 * t + 3], v.w, dot);
+#pragma unroll
+      for (int r = 0; r < kSbarRows; ++r) {  // one fma chain per (a, b), dims in order
+        dot[r] = __builtin_fmaf(q[r][4 * t], v.x, dot[r]);
+        dot[r] = __builtin_fmaf(q[r][4 * t + 1], v.y, dot[r]);
+        dot[r] = __builtin_fmaf(q[r][4 * t + 2], v.z, dot[r]);
+        dot[r] = __builtin_fmaf(q[r][4 * t + 3], v.w, dot[r]);
+      }
     }
-    const float s = dot * scale;
-    sbar[((int64_t)bh * Cq + a) * Ck + b] = s;
-    if (off[b + 1] > off[b]) mx = fmaxf(mx, s);
+    const bool live = off[b + 1] > off[b];
+#pragma unroll
+    for (int r = 0; r < kSbarRows; ++r) {
+      if (a0 + r >= Cq) break;
+      const float sv = dot[r] * scale;
+      sbar[((int64_t)bh * Cq + a0 + r) * Ck + b] = sv;
+      if (live) mx[r] = fmaxf(mx[r], sv);
+    }
   }
-  red[threadIdx.x] = mx;
+#pragma unroll
+  for (int r = 0; r < kSbarRows; ++r) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], o));
+    if (lane == 0) red[r][wave] = mx[r];
+  }
   __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if (threadIdx.x < w) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + w]);
-    __syncthreads();
+  if (threadIdx.x < kSbarRows && a0 + threadIdx.x < Cq) {
+    const int r = threadIdx.x;
+    mrow[(int64_t)bh * Cq + a0 + r] = fmaxf(fmaxf(red[r][0], red[r][1]), fmaxf(red[r][2], red[r][3]));
   }
-  if (threadIdx.x == 0) mrow[(int64_t)bh * Cq + a] = red[0];
 }
 
 template <typename T, int D, bool VALUE_AWARE>
@@ -332,9 +355,11 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
 int run_sbar(const float* qbar, const float* kbar, const int32_t* k_offsets, int BH, int d, int Cq, int Ck,
              float scale, float* sbar, float* mrow, hipStream_t s) {
   if (d == 64)
-    sbar_kernel<64><<<dim3(Cq, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow, nullptr);
+    sbar_kernel<64><<<dim3((unsigned)ceil_div(Cq, kSbarRows), BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale,
+                                                                              sbar, mrow, nullptr);
   else
-    sbar_kernel<128><<<dim3(Cq, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow, nullptr);
+    sbar_kernel<128><<<dim3((unsigned)ceil_div(Cq, kSbarRows), BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale,
+                                                                               sbar, mrow, nullptr);
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;
 }
@@ -346,11 +371,11 @@ int run_probe(const float* qbar, const float* kbar, const float* vbar, const voi
   const bool mfma = dt == SVGEAR_BF16;
   const int rows = mfma ? (int)align_up(Cq, 32) : Cq;
   if (d == 64)
-    sbar_kernel<64><<<dim3(rows, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow,
-                                                   mfma ? q3 : nullptr);
+    sbar_kernel<64><<<dim3((unsigned)ceil_div(rows, kSbarRows), BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale,
+                                                                                sbar, mrow, mfma ? q3 : nullptr);
   else
-    sbar_kernel<128><<<dim3(rows, BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale, sbar, mrow,
-                                                    mfma ? q3 : nullptr);
+    sbar_kernel<128><<<dim3((unsigned)ceil_div(rows, kSbarRows), BH), 256, 0, s>>>(qbar, kbar, k_offsets, Cq, Ck, scale,
+                                                                                 sbar, mrow, mfma ? q3 : nullptr);
   SVGEAR_LAUNCH_CHECK();
   if (mfma) {
     const int64_t stat_stride = probe_stat_stride(Nk);
