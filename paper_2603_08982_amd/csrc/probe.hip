@@ -11,6 +11,8 @@
 // so each key contributes O(1) work per query centroid after its logit, and no term
 // cancels catastrophically when the cluster is tight. |delta_j|^2 and vbar.delta_j do not
 // depend on a and are computed once per key by the whole workgroup.
+#include <type_traits>
+
 #include "common.h"
 
 namespace svgear {
@@ -208,7 +210,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
   return c.b;
 }
 
-// |delta_j|^2 and vbar . delta_j of every clustered key (delta_j = v_j - vbar of its cluster).
+// |delta_j|^2 and -2 vbar . delta_j of every clustered key (delta_j = v_j - vbar of its cluster).
 // One workgroup per (head, key cluster): 16 key slots x 16 lanes of 8 dims.
 template <int D>
 __global__ void __launch_bounds__(256)
@@ -255,17 +257,45 @@ value_stats_kernel(const float* __restrict__ vbar, const bf16_t* __restrict__ vp
       }
       if (lane == 0 && j < end) {
         nd[(int64_t)bh * stat_stride + j] = p_nd;
-        dd[(int64_t)bh * stat_stride + j] = p_dd;
+        dd[(int64_t)bh * stat_stride + j] = -2.0f * p_dd;
       }
     }
   }
 }
 
+// 16 (4) bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16 l
+// (4 l). Inline assembly keeps the compiler from serialising later LDS reads behind the copy;
+// completion is tracked by hand with vmcnt.
+__device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy_4B(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+#define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
 // Block errors with the logits qbar_a . k_j on bf16 MFMAs (qbar in three exact bf16 pieces,
-// so the logits carry fp32-level accuracy). One workgroup per (head, key cluster, group of
-// 128 query centroids); wave w owns query centroids 32w..32w+31 of the group and keeps their
-// operand fragments in registers. The score tile is keys x centroids: a lane holds 16 keys
-// of ONE query centroid per 32-key block, so the block error accumulates lane-locally.
+// so the logits carry fp32-level accuracy). One workgroup per (head, kProbeClusters consecutive
+// key clusters, group of 128 query centroids); wave w owns query centroids 32w..32w+31 of the
+// group and keeps their operand fragments in registers across those key clusters. The score
+// tile is keys x centroids: a lane holds 16 keys of ONE query centroid per 32-key block, so
+// the block error accumulates lane-locally.
+// The 32-key blocks of the workgroup's key clusters form one sequence. Each block is copied
+// once by the whole workgroup, straight from global memory into a ring of kProbeStages LDS
+// buffers, kProbeStages - 1 blocks ahead of the one being computed (the kernel streams every
+// key once and has few workgroups per CU: without that depth too few bytes are in flight),
+// together with its per-key value statistics; the 16-byte chunks of a row are XOR-swizzled
+// with the row index so that the operand reads of 32 rows do not collide. One barrier per
+// block.
+constexpr int kProbeClusters = 4;  // key clusters per workgroup
+constexpr int kProbeStages = 4;    // LDS ring buffers
+
 template <int D, bool VALUE_AWARE>
 __global__ void __launch_bounds__(256)
 block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__ vbar, const bf16_t* __restrict__ kp,
@@ -273,20 +303,29 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
                         const float* __restrict__ mrow, const float* __restrict__ nd, const float* __restrict__ dd,
                         int64_t Nk, int64_t stat_stride, int Cq, int Ck, float scale, float* __restrict__ scores) {
   constexpr int KSN = D / 16;
-  const int b = blockIdx.x, bh = blockIdx.y;
-  const int lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
-  const int ab = blockIdx.z * 4 + (threadIdx.x >> 6), nab = (Cq + 31) >> 5;
-  if (ab >= nab) return;
+  constexpr int CPR = D / 8;             // 16-byte chunks per key row
+  constexpr int RPI = 64 / CPR;          // key rows per copy instruction of a wave
+  constexpr int NCH = 32 / RPI / 4;      // copy instructions per wave per block
+  constexpr int TILE_B = 32 * D * 2;     // bytes of a block in LDS
+  constexpr int LPB = NCH + (VALUE_AWARE ? 1 : 0);  // loads per wave per block
+  constexpr int PF = kProbeStages - 1;   // blocks in flight ahead of the one computed
+  static_assert(32 % (RPI * 4) == 0 && (CPR == 16 || CPR == 8), "tile split / swizzle assume d = 64 or 128");
+  __shared__ __attribute__((aligned(1024))) unsigned char ktile[kProbeStages][TILE_B];
+  __shared__ __attribute__((aligned(256))) float stat[kProbeStages][64];  // [|delta|^2 x 32, vbar.delta x 32]
+  const int bh = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ab = blockIdx.z * 4 + wave, nab = (Cq + 31) >> 5;
+  const bool wave_on = ab < nab;  // waves past the last centroid block still help copying
   const int a = 32 * ab + li;
-  const bool live = a < Cq;
+  const bool live = wave_on && a < Cq;
   const int32_t* off = k_offsets + (int64_t)bh * (Ck + 2);
-  const int start = off[b], end = off[b + 1];
-  if (end <= start) {
-    if (live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + b] = 0.f;
-    return;
-  }
+  const int b_lo = blockIdx.x * kProbeClusters, b_end = min(b_lo + kProbeClusters, Ck);
+  // empty key clusters score 0
+  for (int b = b_lo; b < b_end; ++b)
+    if (off[b + 1] <= off[b] && live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + b] = 0.f;
   bf16x8 bq[3][KSN];
-  {
+  if (wave_on) {
     const bf16_t* src = q3 + (((int64_t)bh * nab + ab) * 3 * KSN) * 512 + lane * 8;
 #pragma unroll
     for (int pc = 0; pc < 3; ++pc)
@@ -295,58 +334,138 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
         bq[pc][s] = as_bf16x8(*reinterpret_cast<const uint4*>(src + (pc * KSN + s) * 512));
   }
   const float m_a = live ? mrow[(int64_t)bh * Cq + a] : 0.f;
-  const float W = live ? __expf(fminf(sbar[((int64_t)bh * Cq + a) * Ck + b] - m_a, kMaxExponent)) : 0.f;
-  float nvb = 0.f;
-  if (VALUE_AWARE) {
-    const float* vb = vbar + ((int64_t)bh * Ck + b) * D;
-    for (int t = 0; t < D; ++t) nvb = __builtin_fmaf(vb[t], vb[t], nvb);
-  }
+  // exponentials as exp2 with the constants folded: e^(x scale - m) = 2^(x scale2 - m2)
+  constexpr float kLog2e = 1.4426950408889634f;
+  const float scale2 = scale * kLog2e, neg_m2 = -m_a * kLog2e, cap2 = kMaxExponent * kLog2e;
+  SVGEAR_WAIT_VMCNT(0);  // from here on vmcnt counts the block copies only
   const bf16_t* kh = kp + (int64_t)bh * Nk * D;
   const float* ndh = nd + (int64_t)bh * stat_stride;
   const float* ddh = dd + (int64_t)bh * stat_stride;
-  float E = 0.f;
-  for (int j0 = start; j0 < end; j0 += 32) {
-    const int jr = min(j0 + li, end - 1);  // A operand: key row li of the block, dims 16s + 8lh..
-    const bf16_t* kr = kh + (int64_t)jr * D + 8 * lh;
-    f32x16 acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < KSN; ++s) {
-      const bf16x8 ak = as_bf16x8(*reinterpret_cast<const uint4*>(kr + 16 * s));
-#pragma unroll
-      for (int pc = 0; pc < 3; ++pc) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[pc][s], acc, 0, 0, 0);
+  const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)&ktile[0][0];
+  const uint32_t lds_s = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)&stat[0][0];
+
+  // position in the sequence of blocks: cluster b, keys j0 .. of [start, end)
+  struct Cursor { int b, start, end, j0; };
+  auto seek = [&](Cursor& c) {  // first non-empty cluster at or after c.b
+    while (c.b < b_end) {
+      c.start = off[c.b];
+      c.end = off[c.b + 1];
+      if (c.end > c.start) break;
+      ++c.b;
     }
-    // register r is key j0 + 8(r/4) + 4lh + r%4, query centroid a
+    c.j0 = c.start;
+  };
+  auto advance = [&](Cursor& c) {
+    c.j0 += 32;
+    if (c.j0 >= c.end) {
+      ++c.b;
+      seek(c);
+    }
+  };
+  // row r of a block keeps its 16-byte chunk c at position c ^ swz(r)
+  auto swz = [](int r) { return CPR == 16 ? (r & 15) : ((r >> 1) & 7); };
+  auto issue = [&](const Cursor& c, int buf) {  // rows past the cluster's end repeat its last key
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int jb = j0 + 8 * g + 4 * lh;
-      float nn[4] = {0.f, 0.f, 0.f, 0.f}, dl[4] = {0.f, 0.f, 0.f, 0.f};
-      if (VALUE_AWARE) {  // arrays are padded past the last key; entries past `end` are unused
+    for (int i = 0; i < NCH; ++i) {
+      const int inst = wave * NCH + i;
+      const int row = inst * RPI + lane / CPR;
+      const int chunk = (lane % CPR) ^ swz(row);
+      const int jr = min(c.j0 + row, c.end - 1);
+      async_copy_16B(kh + (int64_t)jr * D + chunk * 8,
+                     __builtin_amdgcn_readfirstlane(lds_k + buf * TILE_B + inst * 1024));
+    }
+    if (VALUE_AWARE) {  // every wave copies the 64 statistics (same values to the same words)
+      const int j = min(c.j0 + li, c.end - 1);
+      async_copy_4B((lh ? ddh : ndh) + j, __builtin_amdgcn_readfirstlane(lds_s + buf * 256));
+    }
+  };
+
+  Cursor fc{b_lo, 0, 0, 0};  // next block to copy
+  seek(fc);
+  if (fc.b >= b_end) return;  // nothing but empty clusters (uniform over the workgroup)
+  Cursor cc = fc;             // block being computed
+  int issued = 0;
+  for (; issued < PF && fc.b < b_end; ++issued) {
+    issue(fc, issued);
+    advance(fc);
+  }
+  float E = 0.f, W = 0.f, nvb = 0.f;
+  for (int k = 0; cc.b < b_end; ++k) {
+    // block k has landed once at most the copies of the later blocks are outstanding
+    const int ahead = issued - k - 1;
+    if (ahead >= 2) SVGEAR_WAIT_VMCNT(2 * LPB);
+    else if (ahead == 1) SVGEAR_WAIT_VMCNT(LPB);
+    else SVGEAR_WAIT_VMCNT(0);
+    __syncthreads();  // everyone's part of block k is in LDS; everyone is done with block k - 1
+    if (fc.b < b_end) {
+      issue(fc, issued % kProbeStages);
+      advance(fc);
+      ++issued;
+    }
+    const int buf = k % kProbeStages;
+    if (cc.j0 == cc.start) {  // first block of key cluster cc.b
+      E = 0.f;
+      W = live ? __expf(fminf(sbar[((int64_t)bh * Cq + a) * Ck + cc.b] - m_a, kMaxExponent)) : 0.f;
+      nvb = 0.f;
+      if (VALUE_AWARE) {  // |vbar_b|^2: D/64 dims per lane, then across the wave
+        const float* vb = vbar + ((int64_t)bh * Ck + cc.b) * D;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          nn[r] = ndh[jb + r];
-          dl[r] = ddh[jb + r];
-        }
+        for (int t = 0; t < D / 64; ++t) nvb = __builtin_fmaf(vb[lane + 64 * t], vb[lane + 64 * t], nvb);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) nvb += __shfl_xor(nvb, o);
       }
+    }
+    if (wave_on) {
+      // A operand: key row li of the block, dims 16s + 8lh .. = chunk 2s + lh
+      const unsigned char* kr = &ktile[buf][li * (D * 2)];
+      const int key = swz(li);
+      f32x16 acc;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (jb + r < end) {
-          const float w = __expf(fminf(acc[4 * g + r] * scale - m_a, kMaxExponent));
-          const float gdf = W - w;
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KSN; ++s) {
+        const bf16x8 ak = as_bf16x8(*reinterpret_cast<const uint4*>(kr + (((2 * s + lh) ^ key) << 4)));
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[pc][s], acc, 0, 0, 0);
+      }
+      // register r is key j0 + 8(r/4) + 4lh + r%4, query centroid a. Per key, with u = W - w:
+      //   |W vbar - w v_j|^2 = u (u |vbar|^2 - 2 w vbar.delta_j) + w^2 |delta_j|^2
+      auto rank = [&](auto tail_tag) __attribute__((always_inline)) {
+        constexpr bool TAIL = decltype(tail_tag)::value;  // only a cluster's last block has unused rows
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int jb = cc.j0 + 8 * g + 4 * lh;
+          float nn[4] = {0.f, 0.f, 0.f, 0.f}, dl[4] = {0.f, 0.f, 0.f, 0.f};
           if (VALUE_AWARE) {
-            E = __builtin_fmaf(gdf * gdf, nvb, E);
-            E = __builtin_fmaf(-2.0f * gdf * w, dl[r], E);
-            E = __builtin_fmaf(w * w, nn[r], E);
-          } else {
-            E = __builtin_fmaf(gdf, gdf, E);
+            const float4 n4 = *reinterpret_cast<const float4*>(&stat[buf][8 * g + 4 * lh]);
+            const float4 d4 = *reinterpret_cast<const float4*>(&stat[buf][32 + 8 * g + 4 * lh]);
+            nn[0] = n4.x; nn[1] = n4.y; nn[2] = n4.z; nn[3] = n4.w;
+            dl[0] = d4.x; dl[1] = d4.y; dl[2] = d4.z; dl[3] = d4.w;
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (!TAIL || jb + r < cc.end) {
+              const float w = __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(acc[4 * g + r], scale2, neg_m2), cap2));
+              const float u = W - w;
+              if (VALUE_AWARE) {
+                E = __builtin_fmaf(u, __builtin_fmaf(w, dl[r], u * nvb), E);
+                E = __builtin_fmaf(w * w, nn[r], E);
+              } else {
+                E = __builtin_fmaf(u, u, E);
+              }
+            }
           }
         }
+      };
+      if (cc.j0 + 32 <= cc.end) rank(std::false_type{});
+      else rank(std::true_type{});
+      if (cc.j0 + 32 >= cc.end) {  // last block of the cluster
+        const float Et = E + __shfl_xor(E, 32);
+        if (live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + cc.b] = Et / (float)(cc.end - cc.start);
       }
     }
+    advance(cc);
   }
-  E += __shfl_xor(E, 32);
-  if (live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + b] = E / (float)(end - start);
 }
 
 }  // namespace
@@ -381,7 +500,7 @@ int run_probe(const float* qbar, const float* kbar, const float* vbar, const voi
     const int64_t stat_stride = probe_stat_stride(Nk);
     const bf16_t* k16 = static_cast<const bf16_t*>(kp);
     const bf16_t* v16 = static_cast<const bf16_t*>(vp);
-    const dim3 gs(Ck, BH), gb(Ck, BH, (unsigned)ceil_div(ceil_div(Cq, 32), 4));
+    const dim3 gs(Ck, BH), gb((unsigned)ceil_div(Ck, kProbeClusters), BH, (unsigned)ceil_div(ceil_div(Cq, 32), 4));
     if (value_aware) {
       if (d == 64) value_stats_kernel<64><<<gs, 256, 0, s>>>(vbar, v16, k_offsets, Nk, stat_stride, Ck, nd, dd);
       else value_stats_kernel<128><<<gs, 256, 0, s>>>(vbar, v16, k_offsets, Nk, stat_stride, Ck, nd, dd);
