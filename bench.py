@@ -91,28 +91,15 @@ ONE_STREAM = False
 
 
 def run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget, timer=None):
-    """One pass of the whole path (cold k-means start: centroids reset from the seeded init)."""
-    pair = (lambda f, g: (f(), g())) if ONE_STREAM else sv.run_pair
+    """One pass of the whole path (cold k-means start: centroids reset from the seeded init): the
+    binding's attention_layer, which runs Q's k-means beside that of K/V and moves Q's rows while
+    the probe runs (second stream, joined before the attention kernel), so the stage marks on the
+    main stream read: permute = K/V permutation, probe_route = probe + route + the join."""
     cq.copy_(cq0)
     ck.copy_(ck0)
-    scale = float(wl.d) ** -0.5
     if timer: timer.mark("start")
-    # the Q call and the K/V call of a stage are independent: they run side by side on two
-    # streams and are joined before the stage's mark (as attention_layer does)
-    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = pair(lambda: sv.kmeans(Q, cq, wl.iters, wl.n_tail),
-                                                 lambda: sv.kmeans(K, ck, wl.iters, wl.n_tail, x2=V))
-    if timer: timer.mark("kmeans")
-    (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = pair(
-        lambda: sv.permute(lab_q, wl.Cq, [Q], wl.n_tail), lambda: sv.permute(lab_k, wl.Ck, [K, V], wl.n_tail))
-    if timer: timer.mark("permute")
-    r = sv.probe_route(cq, ck, vbar, Kp, Vp, qoff, koff, budget, scale)
-    if timer: timer.mark("probe_route")
-    Op, _ = sv.sparse_attn_comp(Qp, Kp, Vp, ck, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
-    if timer: timer.mark("attention")
-    O = sv.unpermute(Op, perm_q)
-    if timer: timer.mark("unpermute")
-    r.update(O=O, Op=Op, Qp=Qp, Kp=Kp, Vp=Vp, qoff=qoff, koff=koff, perm_q=perm_q, perm_k=perm_k, vbar=vbar,
-             lab_q=lab_q, lab_k=lab_k)
+    O, r = sv.attention_layer(Q, K, V, cq, ck, wl.iters, budget, wl.n_tail, overlap=not ONE_STREAM,
+                              mark=timer.mark if timer else None)
     return r
 
 

@@ -109,6 +109,17 @@ int svgear_permute(const int32_t* labels, int B, int H, int64_t N, int64_t n_tai
                    void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * The row movement of svgear_permute alone: dst[k][bh][p][:] = src[k][b,h,perm[p],:] for a
+ * permutation already computed (svgear_permute with n_tensors = 0 returns perm and offsets
+ * only). For callers that overlap the two halves with other work: the probe needs the
+ * queries' offsets but not the permuted queries, so their rows can move on a second stream
+ * while the probe runs. 1 <= n_tensors <= 4; arguments as in svgear_permute. No workspace.
+ */
+int svgear_permute_rows(const int32_t* perm, int B, int H, int64_t N, int n_tensors,
+                        const void* const* src, const int64_t (*sstride)[3], void* const* dst,
+                        svgear_dtype dt, int d, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * probe + route ("Error-Aware Routing"; Eq. (5), Eq. (7); Algorithm 1).
  *
  * Probe: for query cluster a and non-empty key cluster b,

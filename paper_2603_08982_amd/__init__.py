@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     load_library,
     kmeans,
     permute,
+    permute_rows,
     probe_route,
     sparse_attn_comp,
     unpermute,

@@ -22,7 +22,7 @@ USE_GIVEN_SCORES = 4
 EXPORTED_SYMBOLS = [
     "svgear_version", "svgear_last_hip_error",
     "svgear_kmeans_workspace", "svgear_kmeans",
-    "svgear_permute_workspace", "svgear_permute",
+    "svgear_permute_workspace", "svgear_permute", "svgear_permute_rows",
     "svgear_probe_route_workspace", "svgear_probe_route", "svgear_probe_route_top_p",
     "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp",
     "svgear_sparse_attn_two_stage_workspace", "svgear_sparse_attn_two_stage",
@@ -65,6 +65,9 @@ def load_library():
     lib.svgear_permute.restype = _i
     lib.svgear_permute.argtypes = [_vp, _i, _i, _i64, _i64, _i, _vp, _vp, _i, _c.POINTER(_vp),
                                    _c.POINTER(_I64x3), _c.POINTER(_vp), _i, _i, _vp, _sz, _vp]
+    lib.svgear_permute_rows.restype = _i
+    lib.svgear_permute_rows.argtypes = [_vp, _i, _i, _i64, _i, _c.POINTER(_vp), _c.POINTER(_I64x3), _c.POINTER(_vp),
+                                        _i, _i, _vp]
     lib.svgear_probe_route_workspace.restype = _sz
     lib.svgear_probe_route_workspace.argtypes = [_i, _i, _i64, _i, _i, _i]
     lib.svgear_probe_route.restype = _i
@@ -175,6 +178,25 @@ def permute(labels: torch.Tensor, C: int, tensors: Sequence[torch.Tensor] = (), 
                             _ptr(ws), ws.numel(), _stream())
     _check(rc, "svgear_permute")
     return perm, offsets, outs
+
+
+def permute_rows(perm: torch.Tensor, tensors: Sequence[torch.Tensor]):
+    """svgear_permute_rows: the tensors' rows gathered through an existing permutation."""
+    _need_gpu(perm, *tensors)
+    lib = load_library()
+    B, H, N = perm.shape
+    assert perm.dtype == torch.int32 and perm.is_contiguous() and len(tensors) >= 1
+    d, dt = tensors[0].shape[3], _dt(tensors[0])
+    for t in tensors:
+        assert t.shape == (B, H, N, d) and _dt(t) == dt
+    outs = [torch.empty(B, H, N, d, dtype=t.dtype, device=t.device) for t in tensors]
+    n = len(tensors)
+    src = (_vp * n)(*[t.data_ptr() for t in tensors])
+    dst = (_vp * n)(*[t.data_ptr() for t in outs])
+    sst = (_I64x3 * n)(*[_strides4(t) for t in tensors])
+    rc = lib.svgear_permute_rows(_ptr(perm), B, H, N, n, src, sst, dst, dt, d, _stream())
+    _check(rc, "svgear_permute_rows")
+    return outs
 
 
 def probe_route(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, budget_cost: int, scale: float,
@@ -288,27 +310,73 @@ def run_pair(fn_side, fn_main):
     return a, b
 
 
+def _side_stream(main):
+    side = _SIDE_STREAMS.get(main.device_index)
+    if side is None:
+        side = _SIDE_STREAMS[main.device_index] = torch.cuda.Stream(device=main.device)
+    return side
+
+
 def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tail: int = 0, flags: int = 0,
-                    scale: Optional[float] = None, overlap: bool = True, top_p: Optional[float] = None):
-    """One pass of the whole hot path over a batch of heads: the five library calls in order
-    (with overlap=True the Q and the K/V call of k-means, and then of the permutation, run
-    side by side on two streams).
+                    scale: Optional[float] = None, overlap: bool = True, top_p: Optional[float] = None, mark=None):
+    """One pass of the whole hot path over a batch of heads: k-means, permutation, probe + route,
+    fused attention, un-permutation.
+
+    overlap=True uses a second stream of default priority for work that does not depend on the
+    first stream's: the k-means call of Q runs beside that of K/V, and Q's side of the
+    permutation beside the K/V permutation and the probe: the probe needs the queries' offsets
+    (ready after the short index part) but not the permuted queries, whose rows move while the
+    probe's kernels run. The streams are joined before the fused attention kernel.
 
     init_q [B,H,Cq,d], init_k [B,H,Ck,d] fp32 are the starting centroids (updated in place,
     so a caller can carry them to the next denoising step). With top_p the routing budget is
-    the adaptive per-query-cluster one and budget_cost is ignored. Returns (O, intermediates)."""
+    the adaptive per-query-cluster one and budget_cost is ignored. mark(name), if given, is
+    called on the current stream after each stage ("kmeans", "permute", "probe_route",
+    "attention", "unpermute"). Returns (O, intermediates)."""
     B, H, N, d = Q.shape
     if scale is None:
         scale = float(d) ** -0.5
     Cq, Ck = init_q.shape[2], init_k.shape[2]
-    pair = run_pair if overlap else (lambda f, g: (f(), g()))
-    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = pair(lambda: kmeans(Q, init_q, iters, n_tail),
-                                                 lambda: kmeans(K, init_k, iters, n_tail, x2=V))
-    (perm_q, qoff, (Qp,)), (perm_k, koff, (Kp, Vp)) = pair(lambda: permute(lab_q, Cq, [Q], n_tail),
-                                                           lambda: permute(lab_k, Ck, [K, V], n_tail))
-    r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
+    mark = mark or (lambda name: None)
+    if overlap:
+        (lab_q, qcnt, _), (lab_k, kcnt, vbar) = run_pair(lambda: kmeans(Q, init_q, iters, n_tail),
+                                                         lambda: kmeans(K, init_k, iters, n_tail, x2=V))
+        mark("kmeans")
+        main = torch.cuda.current_stream()
+        side = _side_stream(main)
+        side.wait_stream(main)
+        with torch.cuda.stream(side):
+            perm_q, qoff, _ = permute(lab_q, Cq, [], n_tail)
+            index_done = torch.cuda.Event()
+            index_done.record(side)
+        perm_k, koff, (Kp, Vp) = permute(lab_k, Ck, [K, V], n_tail)
+        mark("permute")
+        # Q's rows move once K's and V's have (all three are bound by memory bandwidth and gain
+        # nothing from sharing it), beside the probe, whose kernels are not
+        kv_done = torch.cuda.Event()
+        kv_done.record(main)
+        with torch.cuda.stream(side):
+            side.wait_event(kv_done)
+            (Qp,) = permute_rows(perm_q, [Q])
+        main.wait_event(index_done)
+        r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
+        main.wait_stream(side)
+        for t in (perm_q, qoff, Qp):
+            t.record_stream(main)
+        mark("probe_route")
+    else:
+        lab_q, qcnt, _ = kmeans(Q, init_q, iters, n_tail)
+        lab_k, kcnt, vbar = kmeans(K, init_k, iters, n_tail, x2=V)
+        mark("kmeans")
+        perm_q, qoff, (Qp,) = permute(lab_q, Cq, [Q], n_tail)
+        perm_k, koff, (Kp, Vp) = permute(lab_k, Ck, [K, V], n_tail)
+        mark("permute")
+        r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
+        mark("probe_route")
     Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
+    mark("attention")
     O = unpermute(Op, perm_q)
+    mark("unpermute")
     r.update(lab_q=lab_q, lab_k=lab_k, qcnt=qcnt, kcnt=kcnt, qbar=init_q, kbar=init_k, vbar=vbar, perm_q=perm_q,
-             perm_k=perm_k, qoff=qoff, koff=koff, Qp=Qp, Kp=Kp, Vp=Vp, Op=Op)
+             perm_k=perm_k, qoff=qoff, koff=koff, Qp=Qp, Kp=Kp, Vp=Vp, Op=Op, O=O)
     return O, r

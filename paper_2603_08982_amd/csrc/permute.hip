@@ -206,6 +206,27 @@ extern "C" size_t svgear_permute_workspace(int B, int H, int64_t N, int C) {
   return align_up((size_t)B * H * sort_chunks(N) * (C + 1) * sizeof(int32_t), 256);
 }
 
+namespace svgear {
+namespace {
+
+// dst[k][bh][p][:] = src[k][b,h,perm[p],:] for every tensor k
+int gather_tensors(const int32_t* perm, int BH, int H, int64_t N, int n_tensors, const void* const* src,
+                   const int64_t (*sstride)[3], void* const* dst, svgear_dtype dt, int d, hipStream_t s) {
+  const int row_units = (int)(d * esize(dt) / 16);
+  const int upe = (int)(16 / esize(dt));  // elements per 16-byte unit
+  for (int k = 0; k < n_tensors; ++k) {
+    Strides st{sstride[k][0] / upe, sstride[k][1] / upe, sstride[k][2] / upe};
+    dim3 grid((unsigned)ceil_div(N * row_units, kThreads), BH);
+    gather_rows_kernel<<<grid, kThreads, 0, s>>>(static_cast<const uint4*>(src[k]), st, H, perm, N, row_units,
+                                                 static_cast<uint4*>(dst[k]));
+    SVGEAR_LAUNCH_CHECK();
+  }
+  return SVGEAR_OK;
+}
+
+}  // namespace
+}  // namespace svgear
+
 extern "C" int svgear_permute(const int32_t* labels, int B, int H, int64_t N, int64_t n_tail, int C,
                               int32_t* perm, int32_t* offsets, int n_tensors, const void* const* src,
                               const int64_t (*sstride)[3], void* const* dst, svgear_dtype dt, int d,
@@ -226,16 +247,19 @@ extern "C" int svgear_permute(const int32_t* labels, int B, int H, int64_t N, in
   const int BH = B * H;
   int rc = sort_labels(labels, BH, N, n_tail, C, perm, offsets, static_cast<int32_t*>(ws), s);
   if (rc != SVGEAR_OK) return rc;
-  const int row_units = (int)(d * esize(dt) / 16);
-  const int upe = (int)(16 / esize(dt));  // elements per 16-byte unit
-  for (int k = 0; k < n_tensors; ++k) {
-    Strides st{sstride[k][0] / upe, sstride[k][1] / upe, sstride[k][2] / upe};
-    dim3 grid((unsigned)ceil_div(N * row_units, kThreads), BH);
-    gather_rows_kernel<<<grid, kThreads, 0, s>>>(static_cast<const uint4*>(src[k]), st, H, perm, N, row_units,
-                                                 static_cast<uint4*>(dst[k]));
-    SVGEAR_LAUNCH_CHECK();
-  }
-  return SVGEAR_OK;
+  return gather_tensors(perm, BH, H, N, n_tensors, src, sstride, dst, dt, d, s);
+}
+
+extern "C" int svgear_permute_rows(const int32_t* perm, int B, int H, int64_t N, int n_tensors,
+                                   const void* const* src, const int64_t (*sstride)[3], void* const* dst,
+                                   svgear_dtype dt, int d, void* stream) {
+  if (!perm || B <= 0 || H <= 0 || N <= 0 || N > INT32_MAX / 2 || n_tensors < 1 || n_tensors > 4 || !src || !dst ||
+      !sstride || (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16))
+    return SVGEAR_ERR_INVALID;
+  for (int k = 0; k < n_tensors; ++k)
+    if (!src[k] || !dst[k] || !strides_ok(sstride[k], esize(dt), src[k]) || reinterpret_cast<uintptr_t>(dst[k]) % 16)
+      return SVGEAR_ERR_INVALID;
+  return gather_tensors(perm, B * H, H, N, n_tensors, src, sstride, dst, dt, d, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int svgear_unpermute(const void* op, const int32_t* perm, svgear_dtype dt, int B, int H, int64_t N,

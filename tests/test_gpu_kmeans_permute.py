@@ -137,6 +137,16 @@ def test_permute_bit_exact_and_roundtrip(name):
     back = sv.unpermute(Kp, perm)
     torch.cuda.synchronize()
     assert torch.equal(back, K)
+    # the two halves on their own: index part without tensors, then the row movement (also from
+    # a strided [B, N, H, d] source)
+    perm2, off2, none = sv.permute(labels, wl.Ck, [], wl.n_tail)
+    K_strided = K.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Kp2, Vp2 = sv.permute_rows(perm2, [K_strided, V.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)])
+    torch.cuda.synchronize()
+    assert none == [] and torch.equal(perm2, perm) and torch.equal(off2, off)
+    assert torch.equal(Kp2, Kp) and torch.equal(Vp2, Vp)
+    with pytest.raises(RuntimeError):
+        sv.permute_rows(perm2.cpu(), [K])
     # strided output: write into a [B, N, H, d] buffer
     buf = torch.zeros(B, N, H, d, dtype=K.dtype, device=dev())
     sv.unpermute(Vp, perm, out=buf.permute(0, 2, 1, 3))
