@@ -118,7 +118,9 @@ def oracle_rows_rel_l2(orc, wl, r, cq, ck, head, n_rows, rng):
     Qs = f(r["Qp"][0, head][torch.from_numpy(rows).to(r["Qp"].device)])
     ref = orc.attention_comp(Qs, f(r["Kp"][0, head]), f(r["Vp"][0, head]), lq_all[rows], lk, kb, vb, mask,
                              orc.scale_of(wl.d), row_chunk=32)
-    got = f(r["Op"][0, head][torch.from_numpy(rows).to(r["Op"].device)])
+    # permuted row p of the output sits at token perm_q[p] (the kernel writes token order)
+    tok = r["perm_q"][0, head][torch.from_numpy(rows).to(r["O"].device)].long()
+    got = f(r["O"][0, head][tok])
     return float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
 
 

@@ -203,6 +203,25 @@ int svgear_sparse_attn_comp(const void* qp, const void* kp, const void* vp, svge
                             float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * svgear_sparse_attn_comp with the un-permutation folded into its epilogue: the kernel's lanes
+ * each write one query row, so sending row p of head bh to token q_perm[bh*Nq + p] costs no
+ * extra pass over the output (svgear_unpermute is then not needed).
+ *   q_perm [BH,Nq] int32 as produced by svgear_permute for the queries
+ *   o [B,H,Nq,d] dt out with element strides ostride = {stride_b, stride_h, stride_n}
+ *     (stride_n >= d, all of them multiples of 16 bytes), token order
+ *   lse [BH,Nq] fp32 out or NULL, token order
+ * Everything else as svgear_sparse_attn_comp (same workspace size).
+ */
+int svgear_sparse_attn_comp_unpermuted(const void* qp, const void* kp, const void* vp,
+                                       svgear_dtype dt, const float* kbar, const float* vbar,
+                                       const int32_t* q_offsets, const int32_t* k_offsets,
+                                       const uint32_t* mask_bits, const int32_t* row_ptr,
+                                       const int32_t* col_idx, const int32_t* q_perm, int B, int H,
+                                       int64_t Nq, int64_t Nk, int d, int Cq, int Ck, float scale,
+                                       void* o, const int64_t ostride[3], float* lse, void* ws,
+                                       size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * The same result in the two-stage form of Algorithm 2, for comparison with the fused kernel:
  * (1) block-sparse exact attention over the routed blocks alone -> (O_r, LSE_r); (2) the
  * pseudo-keys of the skipped clusters alone -> (O_c, LSE_c); (3) merge:

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "svgear_kmeans_workspace", "svgear_kmeans",
     "svgear_permute_workspace", "svgear_permute", "svgear_permute_rows",
     "svgear_probe_route_workspace", "svgear_probe_route", "svgear_probe_route_top_p",
-    "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp",
+    "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp", "svgear_sparse_attn_comp_unpermuted",
     "svgear_sparse_attn_two_stage_workspace", "svgear_sparse_attn_two_stage",
     "svgear_unpermute",
 ]
@@ -81,6 +81,10 @@ def load_library():
     lib.svgear_sparse_attn_comp.restype = _i
     lib.svgear_sparse_attn_comp.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i64,
                                             _i64, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]
+    lib.svgear_sparse_attn_comp_unpermuted.restype = _i
+    lib.svgear_sparse_attn_comp_unpermuted.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i,
+                                                       _i64, _i64, _i, _i, _i, _f, _vp, _c.POINTER(_c.c_int64), _vp,
+                                                       _vp, _sz, _vp]
     lib.svgear_sparse_attn_two_stage_workspace.restype = _sz
     lib.svgear_sparse_attn_two_stage_workspace.argtypes = lib.svgear_sparse_attn_comp_workspace.argtypes
     lib.svgear_sparse_attn_two_stage.restype = _i
@@ -241,23 +245,37 @@ def probe_route(qbar, kbar, vbar, kp, vp, q_offsets, k_offsets, budget_cost: int
 
 
 def sparse_attn_comp(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, scale: float,
-                     want_lse: bool = False, ws: Optional[torch.Tensor] = None, two_stage: bool = False):
+                     want_lse: bool = False, ws: Optional[torch.Tensor] = None, two_stage: bool = False,
+                     q_perm: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
     """svgear_sparse_attn_comp (two_stage=True: svgear_sparse_attn_two_stage, the same result
-    through separate routed / compensation passes and a merge). Returns (op [B,H,Nq,d], lse or None)."""
-    _need_gpu(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx)
+    through separate routed / compensation passes and a merge; q_perm given:
+    svgear_sparse_attn_comp_unpermuted, output and lse in token order, written into `out`
+    [B,H,Nq,d] (any strides with contiguous d) if given). Returns (output [B,H,Nq,d], lse or None)."""
+    _need_gpu(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, q_perm, out)
     lib = load_library()
+    assert not (two_stage and q_perm is not None)
     ws_fn = lib.svgear_sparse_attn_two_stage_workspace if two_stage else lib.svgear_sparse_attn_comp_workspace
-    fn = lib.svgear_sparse_attn_two_stage if two_stage else lib.svgear_sparse_attn_comp
     B, H, Nq, d = qp.shape
     Nk = kp.shape[2]
     Cq = q_offsets.shape[2] - 2
     Ck = k_offsets.shape[2] - 2
     for t in (qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx):
         assert t.is_contiguous()
-    op = torch.empty_like(qp)
     lse = torch.empty(B, H, Nq, dtype=torch.float32, device=qp.device) if want_lse else None
     if ws is None:
         ws = _ws(ws_fn(B, H, Nq, Nk, d, Cq, Ck), qp.device)
+    if q_perm is not None:
+        assert q_perm.is_contiguous() and q_perm.dtype == torch.int32 and q_perm.shape == (B, H, Nq)
+        o = torch.empty_like(qp) if out is None else out
+        assert o.shape == qp.shape and o.dtype == qp.dtype
+        rc = lib.svgear_sparse_attn_comp_unpermuted(
+            _ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar), _ptr(q_offsets), _ptr(k_offsets),
+            _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), _ptr(q_perm), B, H, Nq, Nk, d, Cq, Ck, float(scale), _ptr(o),
+            _strides4(o), _ptr(lse), _ptr(ws), ws.numel(), _stream())
+        _check(rc, "svgear_sparse_attn_comp_unpermuted")
+        return o, lse
+    fn = lib.svgear_sparse_attn_two_stage if two_stage else lib.svgear_sparse_attn_comp
+    op = torch.empty_like(qp)
     rc = fn(_ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar), _ptr(q_offsets), _ptr(k_offsets),
             _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), B, H, Nq, Nk, d, Cq, Ck, float(scale), _ptr(op), _ptr(lse),
             _ptr(ws), ws.numel(), _stream())
@@ -318,7 +336,8 @@ def _side_stream(main):
 
 
 def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tail: int = 0, flags: int = 0,
-                    scale: Optional[float] = None, overlap: bool = True, top_p: Optional[float] = None, mark=None):
+                    scale: Optional[float] = None, overlap: bool = True, top_p: Optional[float] = None, mark=None,
+                    fuse_unpermute: bool = True):
     """One pass of the whole hot path over a batch of heads: k-means, permutation, probe + route,
     fused attention, un-permutation.
 
@@ -332,7 +351,10 @@ def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tai
     so a caller can carry them to the next denoising step). With top_p the routing budget is
     the adaptive per-query-cluster one and budget_cost is ignored. mark(name), if given, is
     called on the current stream after each stage ("kmeans", "permute", "probe_route",
-    "attention", "unpermute"). Returns (O, intermediates)."""
+    "attention", "unpermute"). fuse_unpermute=True lets the attention kernel write its rows
+    straight to token order (svgear_sparse_attn_comp_unpermuted; the "unpermute" stage is then
+    empty and the intermediates hold no permuted output "Op"); False runs svgear_sparse_attn_comp
+    and svgear_unpermute. Returns (O, intermediates)."""
     B, H, N, d = Q.shape
     if scale is None:
         scale = float(d) ** -0.5
@@ -373,10 +395,17 @@ def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tai
         mark("permute")
         r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
         mark("probe_route")
-    Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale)
-    mark("attention")
-    O = unpermute(Op, perm_q)
+    if fuse_unpermute:
+        O, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale,
+                                q_perm=perm_q)
+        mark("attention")
+    else:
+        Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"],
+                                 scale)
+        mark("attention")
+        O = unpermute(Op, perm_q)
+        r["Op"] = Op
     mark("unpermute")
     r.update(lab_q=lab_q, lab_k=lab_k, qcnt=qcnt, kcnt=kcnt, qbar=init_q, kbar=init_k, vbar=vbar, perm_q=perm_q,
-             perm_k=perm_k, qoff=qoff, koff=koff, Qp=Qp, Kp=Kp, Vp=Vp, Op=Op, O=O)
+             perm_k=perm_k, qoff=qoff, koff=koff, Qp=Qp, Kp=Kp, Vp=Vp, O=O)
     return O, r

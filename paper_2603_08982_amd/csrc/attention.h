@@ -36,7 +36,23 @@ struct AttnArgs {
   void* op;
   float* lse;
   int part;  // 0: routed blocks and compensation (fused); 1: routed blocks only; 2: compensation only
+  // token-order output (un-permutation folded into the epilogue): row r of head bh goes to token
+  // out_perm[bh*Nq + r] of a [B,H,Nq,d] tensor with element strides out_st; null = permuted, dense
+  const int32_t* out_perm;
+  Strides out_st;
+  int H;
 };
+
+// Element offset of output row `row` of head bh (and the index of its lse entry).
+__device__ __forceinline__ int64_t out_row_offset(const AttnArgs& p, int bh, int64_t row, int D, int64_t& lse_idx) {
+  if (!p.out_perm) {
+    lse_idx = (int64_t)bh * p.Nq + row;
+    return lse_idx * D;
+  }
+  const int64_t tok = p.out_perm[(int64_t)bh * p.Nq + row];
+  lse_idx = (int64_t)bh * p.Nq + tok;
+  return head_base(p.out_st, bh, p.H) + tok * p.out_st.n;
+}
 
 __device__ __forceinline__ bool mask_bit(const uint32_t* mrow, int b) { return (mrow[b >> 5] >> (b & 31)) & 1u; }
 

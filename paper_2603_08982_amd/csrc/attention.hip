@@ -187,11 +187,12 @@ attn_f32_kernel(AttnArgs p) {
   }
   if (valid) {
     const float inv = l > 0.f ? 1.0f / l : 0.f;
-    float4* o = reinterpret_cast<float4*>(static_cast<float*>(p.op) + ((int64_t)bh * p.Nq + row) * D);
+    int64_t lse_idx;
+    float4* o = reinterpret_cast<float4*>(static_cast<float*>(p.op) + out_row_offset(p, bh, row, D, lse_idx));
 #pragma unroll
     for (int t = 0; t < D / 4; ++t)
       o[t] = make_float4(acc[4 * t] * inv, acc[4 * t + 1] * inv, acc[4 * t + 2] * inv, acc[4 * t + 3] * inv);
-    if (p.lse) p.lse[(int64_t)bh * p.Nq + row] = (m + log2f(l)) * kLn2;
+    if (p.lse) p.lse[lse_idx] = (m + log2f(l)) * kLn2;
   }
 }
 
@@ -215,7 +216,8 @@ extern "C" size_t svgear_sparse_attn_comp_workspace(int B, int H, int64_t Nq, in
 static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype dt, const float* kbar,
                     const float* vbar, const int32_t* q_offsets, const int32_t* k_offsets, const uint32_t* mask_bits,
                     const int32_t* row_ptr, const int32_t* col_idx, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
-                    int Ck, float scale, void* op, float* lse, void* ws, size_t ws_bytes, void* stream, int part) {
+                    int Ck, float scale, void* op, float* lse, void* ws, size_t ws_bytes, void* stream, int part,
+                    const int32_t* out_perm = nullptr, const int64_t* ostride = nullptr) {
   if (!qp || !kp || !vp || !kbar || !vbar || !q_offsets || !k_offsets || !mask_bits || !row_ptr || !col_idx || !op ||
       B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || Cq <= 0 || Ck <= 0 || Cq > 8192 || Ck > 8192 ||
       Nq > INT32_MAX / 2 || Nk > INT32_MAX / 2 || (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) ||
@@ -224,6 +226,15 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   const void* ptrs[] = {qp, kp, vp, kbar, vbar, op};
   for (const void* q : ptrs)
     if (reinterpret_cast<uintptr_t>(q) % 16) return SVGEAR_ERR_INVALID;
+  Strides out_st{0, 0, 0};
+  if (out_perm) {  // token-order output: strides in elements, rows 16-byte aligned
+    const int64_t es = dt == SVGEAR_F32 ? 4 : 2;
+    if (!ostride) return SVGEAR_ERR_INVALID;
+    for (int i = 0; i < 3; ++i)
+      if (ostride[i] < 0 || (ostride[i] * es) % 16) return SVGEAR_ERR_INVALID;
+    if (ostride[2] < d) return SVGEAR_ERR_INVALID;
+    out_st = Strides{ostride[0], ostride[1], ostride[2]};
+  }
   if (!ws || ws_bytes < svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck)) return SVGEAR_ERR_WORKSPACE;
   const int BH = B * H;
   if ((int64_t)BH * ((int64_t)ceil_div(Nq, 64) + Cq + 1) > INT32_MAX / 2) return SVGEAR_ERR_UNSUPPORTED;
@@ -243,7 +254,7 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   SVGEAR_LAUNCH_CHECK();
   AttnArgs a{qp, kp, vp, kbar, vbar, kbar16, vbar16, q_offsets, k_offsets, mask_bits, row_ptr, col_idx,
              tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr,
-             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part};
+             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part, out_perm, out_st, H};
   if (dt == SVGEAR_F32) {
     dim3 grid(max_tiles, BH);
     if (d == 64)
@@ -275,6 +286,18 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
                                        void* stream) {
   return attn_run(qp, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d, Cq,
                   Ck, scale, op, lse, ws, ws_bytes, stream, 0);
+}
+
+extern "C" int svgear_sparse_attn_comp_unpermuted(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
+                                                  const float* kbar, const float* vbar, const int32_t* q_offsets,
+                                                  const int32_t* k_offsets, const uint32_t* mask_bits,
+                                                  const int32_t* row_ptr, const int32_t* col_idx,
+                                                  const int32_t* q_perm, int B, int H, int64_t Nq, int64_t Nk, int d,
+                                                  int Cq, int Ck, float scale, void* o, const int64_t ostride[3],
+                                                  float* lse, void* ws, size_t ws_bytes, void* stream) {
+  if (!q_perm || !ostride) return SVGEAR_ERR_INVALID;
+  return attn_run(qp, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d, Cq,
+                  Ck, scale, o, lse, ws, ws_bytes, stream, 0, q_perm, ostride);
 }
 
 extern "C" size_t svgear_sparse_attn_two_stage_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,

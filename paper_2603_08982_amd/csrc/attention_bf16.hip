@@ -334,7 +334,8 @@ attn_bf16_kernel(AttnArgs p) {
     const float lt = l + __shfl_xor(l, 32);
     if (qvalid) {
       const float inv = lt > 0.f ? 1.0f / lt : 0.f;
-      bf16_t* o = static_cast<bf16_t*>(p.op) + ((int64_t)bh * p.Nq + qrow) * D;
+      int64_t lse_idx;
+      bf16_t* o = static_cast<bf16_t*>(p.op) + out_row_offset(p, bh, qrow, D, lse_idx);
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -344,7 +345,7 @@ attn_bf16_kernel(AttnArgs p) {
           w.y = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
           *reinterpret_cast<uint2*>(o + 32 * db + 8 * g + 4 * lh) = w;
         }
-      if (p.lse && lh == 0) p.lse[(int64_t)bh * p.Nq + qrow] = (m + log2f(lt)) * kLn2;
+      if (p.lse && lh == 0) p.lse[lse_idx] = (m + log2f(lt)) * kLn2;
     }
   }
 }
@@ -854,7 +855,8 @@ attn_bf16_d128_kernel(AttnArgs p) {
     const int qrow = row0 + 32 * wave + li;
     if (qrow < row_end) {
       const float inv = lt > 0.f ? 1.0f / lt : 0.f;
-      bf16_t* o = static_cast<bf16_t*>(p.op) + ((int64_t)bh * p.Nq + qrow) * D;
+      int64_t lse_idx;
+      bf16_t* o = static_cast<bf16_t*>(p.op) + out_row_offset(p, bh, qrow, D, lse_idx);
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -864,7 +866,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
           w.y = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
           *reinterpret_cast<uint2*>(o + 32 * db + 8 * g + 4 * lh) = w;
         }
-      if (p.lse && lh == 0) p.lse[(int64_t)bh * p.Nq + qrow] = (m + log2f(lt)) * kLn2;
+      if (p.lse && lh == 0) p.lse[lse_idx] = (m + log2f(lt)) * kLn2;
     }
   }
 }
