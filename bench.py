@@ -92,15 +92,24 @@ ONE_STREAM = False
 
 def run_layer(sv, Q, K, V, cq0, ck0, cq, ck, wl, budget, timer=None):
     """One pass of the whole path (cold k-means start: centroids reset from the seeded init): the
-    binding's attention_layer, which runs Q's k-means beside that of K/V and moves Q's rows while
-    the probe runs (second stream, joined before the attention kernel), so the stage marks on the
-    main stream read: permute = K/V permutation, probe_route = probe + route + the join."""
+    binding's attention_layer, which runs Q's k-means and permutation index beside those of K/V on
+    a second stream and lets the attention kernel read the queries and write the output in token
+    order through that index (no permuted copy of Q, no separate un-permutation pass)."""
     cq.copy_(cq0)
     ck.copy_(ck0)
     if timer: timer.mark("start")
     O, r = sv.attention_layer(Q, K, V, cq, ck, wl.iters, budget, wl.n_tail, overlap=not ONE_STREAM,
                               mark=timer.mark if timer else None)
+    r["Q"] = Q
     return r
+
+
+def permuted_queries(sv, r):
+    """The layer never materialises the permuted queries (the attention kernel reads Q through the
+    permutation); the sweeps and brackets that call the plain entry point gather them here."""
+    if "Qp" not in r:
+        r["Qp"] = sv.permute_rows(r["perm_q"], [r["Q"]])[0]
+    return r["Qp"]
 
 
 def oracle_rows_rel_l2(orc, wl, r, cq, ck, head, n_rows, rng):
@@ -115,11 +124,11 @@ def oracle_rows_rel_l2(orc, wl, r, cq, ck, head, n_rows, rng):
     mask = bits_to_mask(r["mask_bits"][0, head].cpu().numpy(), wl.Ck)
     kb = np.concatenate([f(ck[0, head]), np.zeros((1, wl.d), np.float32)])
     vb = np.concatenate([f(r["vbar"][0, head]), np.zeros((1, wl.d), np.float32)])
-    Qs = f(r["Qp"][0, head][torch.from_numpy(rows).to(r["Qp"].device)])
+    tok = r["perm_q"][0, head][torch.from_numpy(rows).to(r["O"].device)].long()
+    Qs = f(r["Q"][0, head][tok])
     ref = orc.attention_comp(Qs, f(r["Kp"][0, head]), f(r["Vp"][0, head]), lq_all[rows], lk, kb, vb, mask,
                              orc.scale_of(wl.d), row_chunk=32)
     # permuted row p of the output sits at token perm_q[p] (the kernel writes token order)
-    tok = r["perm_q"][0, head][torch.from_numpy(rows).to(r["O"].device)].long()
     got = f(r["O"][0, head][tok])
     return float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
 
@@ -201,7 +210,7 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
 
     def attend(budget, flags=0):
         pr = sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], budget, scale, flags=flags)
-        return sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"], pr["mask_bits"],
+        return sv.sparse_attn_comp(permuted_queries(sv, r), r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"], pr["mask_bits"],
                                    pr["row_ptr"], pr["col_idx"], scale)[0]
 
     def rel_l2(o, ref):  # per head, then averaged (fp32 on the GPU)
@@ -217,7 +226,7 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
         budget = budget_pairs(rho, wl.N, wl.N)
         t_pr, pr = _time_ms(lambda: sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], budget,
                                                    scale))
-        t_at, at = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
+        t_at, at = _time_ms(lambda: sv.sparse_attn_comp(permuted_queries(sv, r), r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
                                                         pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale))
         dens = float(pr["routed_cost"].sum().item()) / (wl.B * wl.H * float(wl.N) ** 2)
         row = {"rho": rho, "achieved_density": dens, "probe_route_ms": t_pr, "attention_ms": t_at,
@@ -227,7 +236,7 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
         del at
         if 0.0 < rho < 1.0:
             # Algorithm 2's two-stage form (routed pass, compensation pass, merge) on the same mask
-            t_2s, _ = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"],
+            t_2s, _ = _time_ms(lambda: sv.sparse_attn_comp(permuted_queries(sv, r), r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"],
                                                            r["koff"], pr["mask_bits"], pr["row_ptr"], pr["col_idx"],
                                                            scale, two_stage=True))
             row["attention_two_stage_ms"] = t_2s
@@ -241,7 +250,7 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
         def probe_p():
             return sv.probe_route(cq, ck, r["vbar"], r["Kp"], r["Vp"], r["qoff"], r["koff"], 0, scale, top_p=p)
         t_pr, pr = _time_ms(probe_p)
-        t_at, at = _time_ms(lambda: sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
+        t_at, at = _time_ms(lambda: sv.sparse_attn_comp(permuted_queries(sv, r), r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"],
                                                         pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale))
         mean_cost = int(pr["routed_cost"].double().mean().item())
         top_p_rows.append({"top_p": p, "achieved_density": mean_cost / float(wl.N) ** 2, "probe_route_ms": t_pr,
@@ -422,7 +431,7 @@ def main():
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
-        sv.sparse_attn_comp(r["Qp"], r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"], full["mask_bits"],
+        sv.sparse_attn_comp(permuted_queries(sv, r), r["Kp"], r["Vp"], ck, r["vbar"], r["qoff"], r["koff"], full["mask_bits"],
                             full["row_ptr"], full["col_idx"], float(wl.d) ** -0.5)
         e1.record()
         torch.cuda.synchronize()

@@ -203,23 +203,27 @@ int svgear_sparse_attn_comp(const void* qp, const void* kp, const void* vp, svge
                             float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * svgear_sparse_attn_comp with the un-permutation folded into its epilogue: the kernel's lanes
- * each write one query row, so sending row p of head bh to token q_perm[bh*Nq + p] costs no
- * extra pass over the output (svgear_unpermute is then not needed).
- *   q_perm [BH,Nq] int32 as produced by svgear_permute for the queries
- *   o [B,H,Nq,d] dt out with element strides ostride = {stride_b, stride_h, stride_n}
- *     (stride_n >= d, all of them multiples of 16 bytes), token order
+ * svgear_sparse_attn_comp with the queries' permutation folded into the kernel at both ends:
+ * every lane of the kernel reads one whole query row and writes one whole output row, so
+ * taking row p of head bh from token q_perm[bh*Nq + p] of the unpermuted queries, and sending
+ * its result to that token of the output, costs no extra pass (neither the permuted copy of Q
+ * nor svgear_unpermute is then needed; K and V are still streamed from their permuted copies).
+ *   q [B,H,Nq,d] dt, token order, element strides qstride = {stride_b, stride_h, stride_n}
+ *   q_perm [BH,Nq] int32 as produced by svgear_permute for the queries (n_tensors = 0 suffices)
+ *   o [B,H,Nq,d] dt out, token order, element strides ostride
+ *     (stride_n >= d and all strides multiples of 16 bytes, for q and for o)
  *   lse [BH,Nq] fp32 out or NULL, token order
  * Everything else as svgear_sparse_attn_comp (same workspace size).
  */
-int svgear_sparse_attn_comp_unpermuted(const void* qp, const void* kp, const void* vp,
-                                       svgear_dtype dt, const float* kbar, const float* vbar,
-                                       const int32_t* q_offsets, const int32_t* k_offsets,
-                                       const uint32_t* mask_bits, const int32_t* row_ptr,
-                                       const int32_t* col_idx, const int32_t* q_perm, int B, int H,
-                                       int64_t Nq, int64_t Nk, int d, int Cq, int Ck, float scale,
-                                       void* o, const int64_t ostride[3], float* lse, void* ws,
-                                       size_t ws_bytes, void* stream);
+int svgear_sparse_attn_comp_token_order(const void* q, const int64_t qstride[3], const void* kp,
+                                        const void* vp, svgear_dtype dt, const float* kbar,
+                                        const float* vbar, const int32_t* q_offsets,
+                                        const int32_t* k_offsets, const uint32_t* mask_bits,
+                                        const int32_t* row_ptr, const int32_t* col_idx,
+                                        const int32_t* q_perm, int B, int H, int64_t Nq, int64_t Nk,
+                                        int d, int Cq, int Ck, float scale, void* o,
+                                        const int64_t ostride[3], float* lse, void* ws,
+                                        size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * The same result in the two-stage form of Algorithm 2, for comparison with the fused kernel:

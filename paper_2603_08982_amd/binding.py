@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "svgear_kmeans_workspace", "svgear_kmeans",
     "svgear_permute_workspace", "svgear_permute", "svgear_permute_rows",
     "svgear_probe_route_workspace", "svgear_probe_route", "svgear_probe_route_top_p",
-    "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp", "svgear_sparse_attn_comp_unpermuted",
+    "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp", "svgear_sparse_attn_comp_token_order",
     "svgear_sparse_attn_two_stage_workspace", "svgear_sparse_attn_two_stage",
     "svgear_unpermute",
 ]
@@ -81,10 +81,10 @@ def load_library():
     lib.svgear_sparse_attn_comp.restype = _i
     lib.svgear_sparse_attn_comp.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i64,
                                             _i64, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]
-    lib.svgear_sparse_attn_comp_unpermuted.restype = _i
-    lib.svgear_sparse_attn_comp_unpermuted.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i,
-                                                       _i64, _i64, _i, _i, _i, _f, _vp, _c.POINTER(_c.c_int64), _vp,
-                                                       _vp, _sz, _vp]
+    lib.svgear_sparse_attn_comp_token_order.restype = _i
+    lib.svgear_sparse_attn_comp_token_order.argtypes = [_vp, _c.POINTER(_c.c_int64), _vp, _vp, _i, _vp, _vp, _vp, _vp,
+                                                        _vp, _vp, _vp, _vp, _i, _i, _i64, _i64, _i, _i, _i, _f, _vp,
+                                                        _c.POINTER(_c.c_int64), _vp, _vp, _sz, _vp]
     lib.svgear_sparse_attn_two_stage_workspace.restype = _sz
     lib.svgear_sparse_attn_two_stage_workspace.argtypes = lib.svgear_sparse_attn_comp_workspace.argtypes
     lib.svgear_sparse_attn_two_stage.restype = _i
@@ -248,9 +248,10 @@ def sparse_attn_comp(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, ro
                      want_lse: bool = False, ws: Optional[torch.Tensor] = None, two_stage: bool = False,
                      q_perm: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
     """svgear_sparse_attn_comp (two_stage=True: svgear_sparse_attn_two_stage, the same result
-    through separate routed / compensation passes and a merge; q_perm given:
-    svgear_sparse_attn_comp_unpermuted, output and lse in token order, written into `out`
-    [B,H,Nq,d] (any strides with contiguous d) if given). Returns (output [B,H,Nq,d], lse or None)."""
+    through separate routed / compensation passes and a merge).
+    With q_perm: svgear_sparse_attn_comp_token_order: the first argument is then the UNPERMUTED
+    query tensor [B,H,Nq,d] (any strides with contiguous d), and output and lse come in token
+    order, written into `out` if given. Returns (output [B,H,Nq,d], lse or None)."""
     _need_gpu(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, q_perm, out)
     lib = load_library()
     assert not (two_stage and q_perm is not None)
@@ -259,21 +260,22 @@ def sparse_attn_comp(qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, ro
     Nk = kp.shape[2]
     Cq = q_offsets.shape[2] - 2
     Ck = k_offsets.shape[2] - 2
-    for t in (qp, kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx):
+    for t in (kp, vp, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx):
         assert t.is_contiguous()
     lse = torch.empty(B, H, Nq, dtype=torch.float32, device=qp.device) if want_lse else None
     if ws is None:
         ws = _ws(ws_fn(B, H, Nq, Nk, d, Cq, Ck), qp.device)
     if q_perm is not None:
         assert q_perm.is_contiguous() and q_perm.dtype == torch.int32 and q_perm.shape == (B, H, Nq)
-        o = torch.empty_like(qp) if out is None else out
+        o = torch.empty(B, H, Nq, d, dtype=qp.dtype, device=qp.device) if out is None else out
         assert o.shape == qp.shape and o.dtype == qp.dtype
-        rc = lib.svgear_sparse_attn_comp_unpermuted(
-            _ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar), _ptr(q_offsets), _ptr(k_offsets),
-            _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), _ptr(q_perm), B, H, Nq, Nk, d, Cq, Ck, float(scale), _ptr(o),
-            _strides4(o), _ptr(lse), _ptr(ws), ws.numel(), _stream())
-        _check(rc, "svgear_sparse_attn_comp_unpermuted")
+        rc = lib.svgear_sparse_attn_comp_token_order(
+            _ptr(qp), _strides4(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar), _ptr(q_offsets),
+            _ptr(k_offsets), _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), _ptr(q_perm), B, H, Nq, Nk, d, Cq, Ck,
+            float(scale), _ptr(o), _strides4(o), _ptr(lse), _ptr(ws), ws.numel(), _stream())
+        _check(rc, "svgear_sparse_attn_comp_token_order")
         return o, lse
+    assert qp.is_contiguous()
     fn = lib.svgear_sparse_attn_two_stage if two_stage else lib.svgear_sparse_attn_comp
     op = torch.empty_like(qp)
     rc = fn(_ptr(qp), _ptr(kp), _ptr(vp), _dt(qp), _ptr(kbar), _ptr(vbar), _ptr(q_offsets), _ptr(k_offsets),
@@ -328,84 +330,53 @@ def run_pair(fn_side, fn_main):
     return a, b
 
 
-def _side_stream(main):
-    side = _SIDE_STREAMS.get(main.device_index)
-    if side is None:
-        side = _SIDE_STREAMS[main.device_index] = torch.cuda.Stream(device=main.device)
-    return side
-
-
 def attention_layer(Q, K, V, init_q, init_k, iters: int, budget_cost: int, n_tail: int = 0, flags: int = 0,
                     scale: Optional[float] = None, overlap: bool = True, top_p: Optional[float] = None, mark=None,
-                    fuse_unpermute: bool = True):
+                    token_order: bool = True):
     """One pass of the whole hot path over a batch of heads: k-means, permutation, probe + route,
     fused attention, un-permutation.
 
-    overlap=True uses a second stream of default priority for work that does not depend on the
-    first stream's: the k-means call of Q runs beside that of K/V, and Q's side of the
-    permutation beside the K/V permutation and the probe: the probe needs the queries' offsets
-    (ready after the short index part) but not the permuted queries, whose rows move while the
-    probe's kernels run. The streams are joined before the fused attention kernel.
+    token_order=True (default): Q's rows are never moved: only its permutation index is
+    computed, and the attention kernel reads the queries and writes the output through it
+    (svgear_sparse_attn_comp_token_order), so the "unpermute" stage is empty and the
+    intermediates hold neither "Qp" nor "Op". token_order=False materialises Qp, runs
+    svgear_sparse_attn_comp and svgear_unpermute.
+
+    overlap=True uses a second stream of default priority for Q's side of the k-means and
+    permutation stages (they do not depend on K's and V's; the small kernels of one stream fill
+    the gaps of the other), joined before the probe, which needs the queries' offsets.
 
     init_q [B,H,Cq,d], init_k [B,H,Ck,d] fp32 are the starting centroids (updated in place,
     so a caller can carry them to the next denoising step). With top_p the routing budget is
     the adaptive per-query-cluster one and budget_cost is ignored. mark(name), if given, is
     called on the current stream after each stage ("kmeans", "permute", "probe_route",
-    "attention", "unpermute"). fuse_unpermute=True lets the attention kernel write its rows
-    straight to token order (svgear_sparse_attn_comp_unpermuted; the "unpermute" stage is then
-    empty and the intermediates hold no permuted output "Op"); False runs svgear_sparse_attn_comp
-    and svgear_unpermute. Returns (O, intermediates)."""
+    "attention", "unpermute"). Returns (O, intermediates)."""
     B, H, N, d = Q.shape
     if scale is None:
         scale = float(d) ** -0.5
     Cq, Ck = init_q.shape[2], init_k.shape[2]
     mark = mark or (lambda name: None)
-    if overlap:
-        (lab_q, qcnt, _), (lab_k, kcnt, vbar) = run_pair(lambda: kmeans(Q, init_q, iters, n_tail),
-                                                         lambda: kmeans(K, init_k, iters, n_tail, x2=V))
-        mark("kmeans")
-        main = torch.cuda.current_stream()
-        side = _side_stream(main)
-        side.wait_stream(main)
-        with torch.cuda.stream(side):
-            perm_q, qoff, _ = permute(lab_q, Cq, [], n_tail)
-            index_done = torch.cuda.Event()
-            index_done.record(side)
-        perm_k, koff, (Kp, Vp) = permute(lab_k, Ck, [K, V], n_tail)
-        mark("permute")
-        # Q's rows move once K's and V's have (all three are bound by memory bandwidth and gain
-        # nothing from sharing it), beside the probe, whose kernels are not
-        kv_done = torch.cuda.Event()
-        kv_done.record(main)
-        with torch.cuda.stream(side):
-            side.wait_event(kv_done)
-            (Qp,) = permute_rows(perm_q, [Q])
-        main.wait_event(index_done)
-        r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
-        main.wait_stream(side)
-        for t in (perm_q, qoff, Qp):
-            t.record_stream(main)
-        mark("probe_route")
-    else:
-        lab_q, qcnt, _ = kmeans(Q, init_q, iters, n_tail)
-        lab_k, kcnt, vbar = kmeans(K, init_k, iters, n_tail, x2=V)
-        mark("kmeans")
-        perm_q, qoff, (Qp,) = permute(lab_q, Cq, [Q], n_tail)
-        perm_k, koff, (Kp, Vp) = permute(lab_k, Ck, [K, V], n_tail)
-        mark("permute")
-        r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
-        mark("probe_route")
-    if fuse_unpermute:
-        O, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale,
+    pair = run_pair if overlap else (lambda f, g: (f(), g()))
+    (lab_q, qcnt, _), (lab_k, kcnt, vbar) = pair(lambda: kmeans(Q, init_q, iters, n_tail),
+                                                 lambda: kmeans(K, init_k, iters, n_tail, x2=V))
+    mark("kmeans")
+    (perm_q, qoff, q_rows), (perm_k, koff, (Kp, Vp)) = pair(
+        lambda: permute(lab_q, Cq, [] if token_order else [Q], n_tail), lambda: permute(lab_k, Ck, [K, V], n_tail))
+    mark("permute")
+    r = probe_route(init_q, init_k, vbar, Kp, Vp, qoff, koff, budget_cost, scale, flags, top_p=top_p)
+    mark("probe_route")
+    if token_order:
+        O, _ = sparse_attn_comp(Q, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"], scale,
                                 q_perm=perm_q)
         mark("attention")
     else:
+        (Qp,) = q_rows
         Op, _ = sparse_attn_comp(Qp, Kp, Vp, init_k, vbar, qoff, koff, r["mask_bits"], r["row_ptr"], r["col_idx"],
                                  scale)
         mark("attention")
         O = unpermute(Op, perm_q)
-        r["Op"] = Op
+        r.update(Qp=Qp, Op=Op)
     mark("unpermute")
     r.update(lab_q=lab_q, lab_k=lab_k, qcnt=qcnt, kcnt=kcnt, qbar=init_q, kbar=init_k, vbar=vbar, perm_q=perm_q,
-             perm_k=perm_k, qoff=qoff, koff=koff, Qp=Qp, Kp=Kp, Vp=Vp, O=O)
+             perm_k=perm_k, qoff=qoff, koff=koff, Kp=Kp, Vp=Vp, O=O)
     return O, r

@@ -36,20 +36,28 @@ struct AttnArgs {
   void* op;
   float* lse;
   int part;  // 0: routed blocks and compensation (fused); 1: routed blocks only; 2: compensation only
-  // token-order output (un-permutation folded into the epilogue): row r of head bh goes to token
-  // out_perm[bh*Nq + r] of a [B,H,Nq,d] tensor with element strides out_st; null = permuted, dense
-  const int32_t* out_perm;
-  Strides out_st;
+  // token order at both ends (the queries' permutation folded into the kernel, whose lanes read
+  // and write whole rows anyway): row r of head bh is token tok_perm[bh*Nq + r] of the query
+  // tensor (element strides q_st) and of the output tensor (out_st), both [B,H,Nq,d];
+  // null = qp and op are permuted and dense
+  const int32_t* tok_perm;
+  Strides q_st, out_st;
   int H;
 };
 
+// Element offset of query row `row` of head bh.
+__device__ __forceinline__ int64_t q_row_offset(const AttnArgs& p, int bh, int64_t row, int D) {
+  if (!p.tok_perm) return ((int64_t)bh * p.Nq + row) * D;
+  return head_base(p.q_st, bh, p.H) + (int64_t)p.tok_perm[(int64_t)bh * p.Nq + row] * p.q_st.n;
+}
+
 // Element offset of output row `row` of head bh (and the index of its lse entry).
 __device__ __forceinline__ int64_t out_row_offset(const AttnArgs& p, int bh, int64_t row, int D, int64_t& lse_idx) {
-  if (!p.out_perm) {
+  if (!p.tok_perm) {
     lse_idx = (int64_t)bh * p.Nq + row;
     return lse_idx * D;
   }
-  const int64_t tok = p.out_perm[(int64_t)bh * p.Nq + row];
+  const int64_t tok = p.tok_perm[(int64_t)bh * p.Nq + row];
   lse_idx = (int64_t)bh * p.Nq + tok;
   return head_base(p.out_st, bh, p.H) + tok * p.out_st.n;
 }

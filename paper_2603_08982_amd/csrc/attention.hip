@@ -74,13 +74,13 @@ attn_f32_kernel(AttnArgs p) {
   const int row_end = qo[a + 1];
   const int row = row0 + tid;
   const bool valid = row < row_end;
-  const float* qh = static_cast<const float*>(p.qp) + (int64_t)bh * p.Nq * D;
   const float* kh = static_cast<const float*>(p.kp) + (int64_t)bh * p.Nk * D;
   const float* vh = static_cast<const float*>(p.vp) + (int64_t)bh * p.Nk * D;
   const float c = p.scale * kLog2e;
   float q[D], acc[D];
   {
-    const float4* qr = reinterpret_cast<const float4*>(qh + (int64_t)(valid ? row : row_end - 1) * D);
+    const float4* qr = reinterpret_cast<const float4*>(static_cast<const float*>(p.qp) +
+                                                       q_row_offset(p, bh, valid ? row : row_end - 1, D));
 #pragma unroll
     for (int t = 0; t < D / 4; ++t) {
       const float4 v = qr[t];
@@ -217,7 +217,8 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
                     const float* vbar, const int32_t* q_offsets, const int32_t* k_offsets, const uint32_t* mask_bits,
                     const int32_t* row_ptr, const int32_t* col_idx, int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
                     int Ck, float scale, void* op, float* lse, void* ws, size_t ws_bytes, void* stream, int part,
-                    const int32_t* out_perm = nullptr, const int64_t* ostride = nullptr) {
+                    const int32_t* tok_perm = nullptr, const int64_t* qstride = nullptr,
+                    const int64_t* ostride = nullptr) {
   if (!qp || !kp || !vp || !kbar || !vbar || !q_offsets || !k_offsets || !mask_bits || !row_ptr || !col_idx || !op ||
       B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || Cq <= 0 || Ck <= 0 || Cq > 8192 || Ck > 8192 ||
       Nq > INT32_MAX / 2 || Nk > INT32_MAX / 2 || (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) ||
@@ -226,13 +227,15 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   const void* ptrs[] = {qp, kp, vp, kbar, vbar, op};
   for (const void* q : ptrs)
     if (reinterpret_cast<uintptr_t>(q) % 16) return SVGEAR_ERR_INVALID;
-  Strides out_st{0, 0, 0};
-  if (out_perm) {  // token-order output: strides in elements, rows 16-byte aligned
+  Strides q_st{0, 0, 0}, out_st{0, 0, 0};
+  if (tok_perm) {  // token order at both ends: strides in elements, rows 16-byte aligned
     const int64_t es = dt == SVGEAR_F32 ? 4 : 2;
-    if (!ostride) return SVGEAR_ERR_INVALID;
+    if (!qstride || !ostride) return SVGEAR_ERR_INVALID;
     for (int i = 0; i < 3; ++i)
-      if (ostride[i] < 0 || (ostride[i] * es) % 16) return SVGEAR_ERR_INVALID;
-    if (ostride[2] < d) return SVGEAR_ERR_INVALID;
+      if (qstride[i] < 0 || (qstride[i] * es) % 16 || ostride[i] < 0 || (ostride[i] * es) % 16)
+        return SVGEAR_ERR_INVALID;
+    if (qstride[2] < d || ostride[2] < d) return SVGEAR_ERR_INVALID;
+    q_st = Strides{qstride[0], qstride[1], qstride[2]};
     out_st = Strides{ostride[0], ostride[1], ostride[2]};
   }
   if (!ws || ws_bytes < svgear_sparse_attn_comp_workspace(B, H, Nq, Nk, d, Cq, Ck)) return SVGEAR_ERR_WORKSPACE;
@@ -254,7 +257,7 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   SVGEAR_LAUNCH_CHECK();
   AttnArgs a{qp, kp, vp, kbar, vbar, kbar16, vbar16, q_offsets, k_offsets, mask_bits, row_ptr, col_idx,
              tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr,
-             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part, out_perm, out_st, H};
+             Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part, tok_perm, q_st, out_st, H};
   if (dt == SVGEAR_F32) {
     dim3 grid(max_tiles, BH);
     if (d == 64)
@@ -288,16 +291,17 @@ extern "C" int svgear_sparse_attn_comp(const void* qp, const void* kp, const voi
                   Ck, scale, op, lse, ws, ws_bytes, stream, 0);
 }
 
-extern "C" int svgear_sparse_attn_comp_unpermuted(const void* qp, const void* kp, const void* vp, svgear_dtype dt,
-                                                  const float* kbar, const float* vbar, const int32_t* q_offsets,
-                                                  const int32_t* k_offsets, const uint32_t* mask_bits,
-                                                  const int32_t* row_ptr, const int32_t* col_idx,
-                                                  const int32_t* q_perm, int B, int H, int64_t Nq, int64_t Nk, int d,
-                                                  int Cq, int Ck, float scale, void* o, const int64_t ostride[3],
-                                                  float* lse, void* ws, size_t ws_bytes, void* stream) {
-  if (!q_perm || !ostride) return SVGEAR_ERR_INVALID;
-  return attn_run(qp, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d, Cq,
-                  Ck, scale, o, lse, ws, ws_bytes, stream, 0, q_perm, ostride);
+extern "C" int svgear_sparse_attn_comp_token_order(const void* q, const int64_t qstride[3], const void* kp,
+                                                   const void* vp, svgear_dtype dt, const float* kbar,
+                                                   const float* vbar, const int32_t* q_offsets,
+                                                   const int32_t* k_offsets, const uint32_t* mask_bits,
+                                                   const int32_t* row_ptr, const int32_t* col_idx,
+                                                   const int32_t* q_perm, int B, int H, int64_t Nq, int64_t Nk, int d,
+                                                   int Cq, int Ck, float scale, void* o, const int64_t ostride[3],
+                                                   float* lse, void* ws, size_t ws_bytes, void* stream) {
+  if (!q_perm || !qstride || !ostride) return SVGEAR_ERR_INVALID;
+  return attn_run(q, kp, vp, dt, kbar, vbar, q_offsets, k_offsets, mask_bits, row_ptr, col_idx, B, H, Nq, Nk, d, Cq,
+                  Ck, scale, o, lse, ws, ws_bytes, stream, 0, q_perm, qstride, ostride);
 }
 
 extern "C" size_t svgear_sparse_attn_two_stage_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,

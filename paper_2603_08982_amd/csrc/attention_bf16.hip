@@ -214,7 +214,7 @@ attn_bf16_kernel(AttnArgs p) {
   const bool wave_active = (row0 + 32 * wave) < row_end;
   bf16x8 bq[KS];
   {
-    const bf16_t* qr = static_cast<const bf16_t*>(p.qp) + ((int64_t)bh * p.Nq + (qvalid ? qrow : row_end - 1)) * D;
+    const bf16_t* qr = static_cast<const bf16_t*>(p.qp) + q_row_offset(p, bh, qvalid ? qrow : row_end - 1, D);
 #pragma unroll
     for (int s = 0; s < KS; ++s) bq[s] = as_bf16x8(*reinterpret_cast<const uint4*>(qr + 16 * s + 8 * lh));
   }
@@ -607,7 +607,7 @@ attn_bf16_d128_kernel(AttnArgs p) {
   bf16x8 bq[KS];
   {
     const int qrow = row0 + 32 * wave + li;
-    const bf16_t* qr = static_cast<const bf16_t*>(p.qp) + ((int64_t)bh * p.Nq + (qrow < row_end ? qrow : row_end - 1)) * D;
+    const bf16_t* qr = static_cast<const bf16_t*>(p.qp) + q_row_offset(p, bh, qrow < row_end ? qrow : row_end - 1, D);
 #pragma unroll
     for (int s = 0; s < KS; ++s) bq[s] = as_bf16x8(*reinterpret_cast<const uint4*>(qr + 16 * s + 8 * lh));
   }

@@ -167,7 +167,7 @@ def test_end_to_end_chain_matches_oracle(name):
             m = bits_to_mask(to_np(r["mask_bits"][b, h]), wl.Ck)
             kb = np.concatenate([to_np(r["kbar"][b, h]), np.zeros((1, wl.d), np.float32)])
             vb = np.concatenate([to_np(r["vbar"][b, h]), np.zeros((1, wl.d), np.float32)])
-            op_ref = orc.attention_comp(to_np(r["Qp"][b, h]), to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
+            op_ref = orc.attention_comp(to_np(Q[b, h])[to_np(r["perm_q"][b, h])], to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
                                         vb, m, orc.scale_of(wl.d))
             o_ref = orc.unpermute_rows(op_ref, to_np(r["perm_q"][b, h]))
             assert rel_l2(to_np(O[b, h]), o_ref) <= TOL[wl.dtype]
@@ -222,38 +222,40 @@ def test_end_to_end_chain_with_adaptive_row_budgets_matches_oracle(name):
             lk = np.repeat(np.arange(wl.Ck + 1), np.diff(to_np(r["koff"][b, h])))
             kb = np.concatenate([to_np(r["kbar"][b, h]), np.zeros((1, wl.d), np.float32)])
             vb = np.concatenate([to_np(r["vbar"][b, h]), np.zeros((1, wl.d), np.float32)])
-            op_ref = orc.attention_comp(to_np(r["Qp"][b, h]), to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
+            op_ref = orc.attention_comp(to_np(Q[b, h])[to_np(r["perm_q"][b, h])], to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
                                         vb, m, scale)
             assert rel_l2(to_np(O[b, h]), orc.unpermute_rows(op_ref, to_np(r["perm_q"][b, h]))) <= TOL[wl.dtype]
 
 
 @pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_f32_d128"])
 def test_token_order_entry_equals_permuted_entry_plus_unpermute(name):
-    """svgear_sparse_attn_comp_unpermuted writes the rows svgear_sparse_attn_comp computes (parity
-    with the oracle is tested above) to their tokens: bitwise equal to that call followed by
-    svgear_unpermute, also into a strided [B, N, H, d] buffer, lse in token order; and the whole
-    layer gives the same output with and without the folded un-permutation."""
+    """svgear_sparse_attn_comp_token_order reads the queries and writes the rows
+    svgear_sparse_attn_comp computes (parity with the oracle is tested above) through the
+    queries' permutation: bitwise equal to gathering Q, that call and svgear_unpermute, also from
+    and into strided [B, N, H, d] buffers, lse in token order; and the whole layer gives the
+    same output either way."""
     wl = get_workload(name)
     Q, K, V = make_qkv(wl, dev())
     B, H, N, d = Q.shape
     cq = init_centroids(Q, wl.Cq, wl.seed, 0, wl.n_tail)
     ck = init_centroids(K, wl.Ck, wl.seed, 1, wl.n_tail)
     budget = budget_pairs(wl.rho, wl.N, wl.N)
-    O_sep, r = sv.attention_layer(Q, K, V, cq.clone(), ck.clone(), wl.iters, budget, wl.n_tail, fuse_unpermute=False)
-    O_fused, r2 = sv.attention_layer(Q, K, V, cq.clone(), ck.clone(), wl.iters, budget, wl.n_tail)
+    O_sep, r = sv.attention_layer(Q, K, V, cq.clone(), ck.clone(), wl.iters, budget, wl.n_tail, token_order=False)
+    O_tok, r2 = sv.attention_layer(Q, K, V, cq.clone(), ck.clone(), wl.iters, budget, wl.n_tail)
     torch.cuda.synchronize()
-    assert "Op" in r and "Op" not in r2
-    assert torch.equal(O_sep, O_fused)
+    assert "Op" in r and "Qp" in r and "Op" not in r2 and "Qp" not in r2
+    assert torch.equal(O_sep, O_tok)
     assert torch.equal(O_sep, sv.unpermute(r["Op"], r["perm_q"]))
-    args = (r["Qp"], r["Kp"], r["Vp"], r["kbar"], r["vbar"], r["qoff"], r["koff"], r["mask_bits"], r["row_ptr"],
-            r["col_idx"], orc.scale_of(wl.d))
-    op, lse_p = sv.sparse_attn_comp(*args, want_lse=True)
+    rest = (r["Kp"], r["Vp"], r["kbar"], r["vbar"], r["qoff"], r["koff"], r["mask_bits"], r["row_ptr"], r["col_idx"],
+            orc.scale_of(wl.d))
+    op, lse_p = sv.sparse_attn_comp(r["Qp"], *rest, want_lse=True)
+    Q_strided = Q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
     buf = torch.zeros(B, N, H, d, dtype=Q.dtype, device=dev())
-    o, lse_t = sv.sparse_attn_comp(*args, want_lse=True, q_perm=r["perm_q"], out=buf.permute(0, 2, 1, 3))
+    o, lse_t = sv.sparse_attn_comp(Q_strided, *rest, want_lse=True, q_perm=r["perm_q"], out=buf.permute(0, 2, 1, 3))
     torch.cuda.synchronize()
     assert torch.equal(buf.permute(0, 2, 1, 3), O_sep)
     idx = r["perm_q"].long()
     assert torch.equal(torch.gather(lse_t, 2, idx), lse_p)
     with pytest.raises(RuntimeError):  # rows of the output must be 16-byte aligned
         bad = torch.zeros(B, H, N, d + 1, dtype=Q.dtype, device=dev())[..., :d]
-        sv.sparse_attn_comp(*args, q_perm=r["perm_q"], out=bad)
+        sv.sparse_attn_comp(Q, *rest, q_perm=r["perm_q"], out=bad)

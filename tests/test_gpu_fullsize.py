@@ -102,7 +102,7 @@ def test_full_size_layer_sampled_parity(name, top_p):
         lk = np.repeat(np.arange(wl.Ck + 1), np.diff(koff))
         kb = np.concatenate([kbar, np.zeros((1, wl.d), np.float32)])
         vb = np.concatenate([vbar, np.zeros((1, wl.d), np.float32)])
-        Qs = to_np(r["Qp"][0, h][torch.from_numpy(rows).to(dev())])
+        Qs = to_np(Q[0, h][torch.from_numpy(pq[rows]).long().to(dev())])
         ref = orc.attention_comp(Qs, Kp, Vp, lq[rows], lk, kb, vb, mask, scale, row_chunk=16)
         # the kernel writes row p of the permuted order to token perm_q[p] (un-permutation folded
         # into its epilogue): permuted row p is O[perm_q[p]]

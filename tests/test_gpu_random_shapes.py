@@ -66,7 +66,7 @@ def test_random_shape_layer_matches_oracle(seed):
             lk = np.repeat(np.arange(wl.Ck + 1), np.diff(ok))
             kb = np.concatenate([to_np(r["kbar"][b, h]), np.zeros((1, wl.d), np.float32)])
             vb = np.concatenate([to_np(r["vbar"][b, h]), np.zeros((1, wl.d), np.float32)])
-            op_ref = orc.attention_comp(to_np(r["Qp"][b, h]), to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
+            op_ref = orc.attention_comp(to_np(Q[b, h])[pq], to_np(r["Kp"][b, h]), to_np(r["Vp"][b, h]), lq, lk, kb,
                                         vb, mask, scale)
             # the layer's attention kernel writes straight to token order: permuted row p is O[pq[p]]
             assert rel_l2(to_np(O[b, h])[pq], op_ref) <= 1e-2, f"{wl}"
