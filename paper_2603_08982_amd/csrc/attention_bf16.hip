@@ -881,41 +881,60 @@ plan_items_kernel(const int32_t* __restrict__ q_offsets, const int32_t* __restri
                   const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int Cq, int Ck, int BM,
                   int32_t* __restrict__ item_T, int32_t* __restrict__ item_nt) {
   const int bh = blockIdx.x, R = Cq + 1, Cc = Ck + 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t* qo = q_offsets + (int64_t)bh * (Cq + 2);
   const int32_t* ko = k_offsets + (int64_t)bh * (Ck + 2);
   const int32_t* rp = row_ptr + (int64_t)bh * (R + 1);
-  for (int a = threadIdx.x; a < R; a += 256) {
+  // a wave per query cluster, its lanes over the routed key clusters
+  for (int a = wave; a < R; a += 4) {
     const int n = qo[a + 1] - qo[a];
     const int32_t* ci = col_idx + (int64_t)bh * R * Cc + rp[a];
     const int ne = rp[a + 1] - rp[a];
     int64_t nr = 0;
-    for (int e = 0; e < ne; ++e) {
+    for (int e = lane; e < ne; e += 64) {
       const int b = ci[e];
       const int sz = ko[b + 1] - ko[b];
       nr += sz > 0 ? sz : 0;
     }
-    const int nt = n > 0 ? (n + BM - 1) / BM : 0;
-    item_nt[bh * R + a] = nt;
-    item_T[bh * R + a] = nt > 0 ? (int)((nr + BN - 1) / BN) + (a < Cq ? (Ck + BN - 1) / BN : 0) : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) nr += __shfl_xor(nr, o);
+    if (lane == 0) {
+      const int nt = n > 0 ? (n + BM - 1) / BM : 0;
+      item_nt[bh * R + a] = nt;
+      item_T[bh * R + a] = nt > 0 ? (int)((nr + BN - 1) / BN) + (a < Cq ? (Ck + BN - 1) / BN : 0) : 0;
+    }
   }
 }
 
+// Rank of every item by (T descending, index ascending), by counting: a workgroup ranks 64 items,
+// each of its four waves counting over a quarter of all items.
+constexpr int kRankItems = 64;
 __global__ void __launch_bounds__(256)
 plan_rank_kernel(const int32_t* __restrict__ item_T, int M, int32_t* __restrict__ by_rank) {
-  __shared__ uint64_t keys[256];
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  __shared__ uint64_t keys[4][64];
+  __shared__ int rank_sum[kRankItems];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = blockIdx.x * kRankItems + lane;
   // larger key = earlier: T descending, then index ascending
-  const uint64_t mine = i < M ? ((uint64_t)(uint32_t)item_T[i] << 32) | (uint32_t)(0x7fffffff - i) : 0;
+  auto key_of = [&](int j) {
+    return j < M ? ((uint64_t)(uint32_t)item_T[j] << 32) | (uint32_t)(0x7fffffff - j) : (uint64_t)0;
+  };
+  const uint64_t mine = key_of(i);
+  if (threadIdx.x < kRankItems) rank_sum[threadIdx.x] = 0;
+  __syncthreads();
+  const int quarter = (M + 3) / 4;
+  const int j_lo = wave * quarter, j_hi = min(j_lo + quarter, M);
   int rank = 0;
-  for (int j0 = 0; j0 < M; j0 += 256) {
-    const int j = j0 + threadIdx.x;
-    keys[threadIdx.x] = j < M ? ((uint64_t)(uint32_t)item_T[j] << 32) | (uint32_t)(0x7fffffff - j) : 0;
-    __syncthreads();
-    const int lim = M - j0 < 256 ? M - j0 : 256;
-    for (int u = 0; u < lim; ++u) rank += keys[u] > mine;
-    __syncthreads();
+  for (int j0 = j_lo; j0 < j_hi; j0 += 64) {  // the wave's own tile of keys: no workgroup barrier needed
+    keys[wave][lane] = j0 + lane < j_hi ? key_of(j0 + lane) : (uint64_t)0;
+    __builtin_amdgcn_wave_barrier();
+    const int lim = min(64, j_hi - j0);
+    for (int u = 0; u < lim; ++u) rank += keys[wave][u] > mine;
+    __builtin_amdgcn_wave_barrier();
   }
-  if (i < M) by_rank[rank] = i;
+  atomicAdd(&rank_sum[lane], rank);
+  __syncthreads();
+  if (wave == 0 && i < M) by_rank[rank_sum[lane]] = i;
 }
 
 // rank r -> (list, position): round r/8 deals one item to every list, odd rounds in reverse
@@ -1013,7 +1032,7 @@ int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
   if (!w.ok()) return SVGEAR_ERR_WORKSPACE;
   plan_items_kernel<<<a.BH, 256, 0, s>>>(a.q_offsets, a.k_offsets, a.row_ptr, a.col_idx, a.Cq, a.Ck, BM, item_T, item_nt);
   SVGEAR_LAUNCH_CHECK();
-  plan_rank_kernel<<<(unsigned)ceil_div(M, 256), 256, 0, s>>>(item_T, M, by_rank);
+  plan_rank_kernel<<<(unsigned)ceil_div(M, kRankItems), 256, 0, s>>>(item_T, M, by_rank);
   SVGEAR_LAUNCH_CHECK();
   plan_lists_kernel<<<1, 1024, 0, s>>>(a.q_offsets, item_nt, by_rank, M, a.Cq, BM, rank_off, sched_bh, sched_a, sched_row0,
                                       sched_x);
