@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # 1 GiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); only known for the default configuration of a workload.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {("wan", 0.25): 41.87e9}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {("wan", 0.25): 41.82e9}
 
 
 def parse():
