@@ -374,6 +374,10 @@ int probe_route_impl(const float* qbar, const float* kbar, const float* vbar, co
   }
   const int per_row = (adaptive || (flags & SVGEAR_ROUTE_PER_ROW)) ? 1 : 0;
   if (adaptive) {
+    // up to 64 KB of weights for the largest Ck, beside the kernel's static LDS
+    SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(top_p_budget_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)((size_t)Ck * sizeof(unsigned long long))));
     top_p_budget_kernel<<<dim3(Cq, BH), kTopPThreads, (size_t)Ck * sizeof(unsigned long long), s>>>(
         sbar, mrow, q_offsets, k_offsets, Cq, Ck, top_p, row_budget);
     SVGEAR_LAUNCH_CHECK();

@@ -174,3 +174,39 @@ def test_top_p_argument_checks():
             sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, top_p=bad)
     with pytest.raises(RuntimeError):
         sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, flags=sv.ROUTE_PER_ROW, top_p=0.5)
+
+
+def test_route_with_thousands_of_key_clusters():
+    """The router at the upper end of the cluster counts the ABI accepts (Ck = 7000 of 8192):
+    one budget per head and the adaptive row budgets, from injected scores, bit-exact."""
+    rng = np.random.default_rng(4)
+    Cq, Ck, d, N = 5, 7000, 64, 8000
+    lab_k = torch.from_numpy((rng.permutation(N) % Ck).astype(np.int32))[None, None].to(dev())
+    lab_q = torch.from_numpy(rng.integers(0, Cq, N).astype(np.int32))[None, None].to(dev())
+    perm_q, qoff, _ = sv.permute(lab_q, Cq)
+    perm_k, koff, _ = sv.permute(lab_k, Ck)
+    qbar = torch.from_numpy(rng.standard_normal((1, 1, Cq, d)).astype(np.float32)).to(dev())
+    kbar = torch.from_numpy((0.3 * rng.standard_normal((1, 1, Ck, d))).astype(np.float32)).to(dev())
+    vbar = torch.zeros_like(kbar)
+    Kp = torch.zeros(1, 1, N, d, dtype=torch.bfloat16, device=dev())
+    scores = torch.from_numpy(rng.random((1, 1, Cq, Ck)).astype(np.float32)).to(dev())
+    q_sizes, k_sizes = np.diff(to_np(qoff[0, 0])[: Cq + 1]), np.diff(to_np(koff[0, 0])[: Ck + 1])
+    scale = orc.scale_of(d)
+    budget = N * N // 5
+    r = sv.probe_route(qbar, kbar, vbar, Kp, Kp, qoff, koff, budget, scale, flags=sv.USE_GIVEN_SCORES,
+                       scores=scores.clone())
+    t = sv.probe_route(qbar, kbar, vbar, Kp, Kp, qoff, koff, 0, scale, flags=sv.USE_GIVEN_SCORES,
+                       scores=scores.clone(), top_p=0.5)
+    torch.cuda.synchronize()
+    m_ref, _, _, cost_ref = orc.route(to_np(scores[0, 0]), q_sizes, k_sizes, budget)
+    assert np.array_equal(bits_to_mask(to_np(r["mask_bits"][0, 0]), Ck), full_mask(m_ref, Cq, Ck))
+    assert int(r["routed_cost"][0, 0]) == cost_ref
+    ref_head = dict(qbar=to_np(qbar[0, 0]), kbar=to_np(kbar[0, 0]), qcnt=q_sizes, kcnt=k_sizes)
+    got = to_np(t["row_budget"][0, 0])
+
+    class _W:  # what _check_row_budgets reads of a workload
+        pass
+    _check_row_budgets(got, ref_head, _W(), 0.5, scale)
+    m_ref, _, _, cost_ref = orc.route(to_np(scores[0, 0]), q_sizes, k_sizes, 0, row_budgets=got)
+    assert np.array_equal(bits_to_mask(to_np(t["mask_bits"][0, 0]), Ck), full_mask(m_ref, Cq, Ck))
+    assert int(t["routed_cost"][0, 0]) == cost_ref
