@@ -189,6 +189,10 @@ int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C,
   dim3 grid(nchunks, BH);
   hist_kernel<<<grid, kThreads, (C + 1) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks, chunk_hist);
   SVGEAR_LAUNCH_CHECK();
+  // two tables of C+1 counters: a few bytes over the default 64 KB at the largest C
+  SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(scan_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)(2 * (C + 1) * sizeof(int32_t))));
   scan_kernel<<<BH, kThreads, 2 * (C + 1) * sizeof(int32_t), s>>>(chunk_hist, N, C, nchunks, offsets);
   SVGEAR_LAUNCH_CHECK();
   scatter_kernel<<<grid, kThreads, (C + 1) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks,

@@ -165,3 +165,27 @@ def test_permute_large_chunks_and_many_clusters():
         p_ref, o_ref = orc.permute(to_np(labels[0, h]), C, 0)
         assert np.array_equal(to_np(perm[0, h]), p_ref)
         assert np.array_equal(to_np(off[0, h]), o_ref)
+
+
+def test_largest_cluster_count_the_abi_accepts():
+    """C = 8192, the upper limit of svgear_kmeans / svgear_permute: permutation bit-exact, and
+    two k-means iterations (bf16, d = 64) in lock-step with the oracle."""
+    g = torch.Generator(device="cpu").manual_seed(23)
+    N, C, d = 8192 + 700, 8192, 64
+    labels = torch.randint(0, C, (1, 1, N), generator=g, dtype=torch.int32).to(dev())
+    perm, off, _ = sv.permute(labels, C)
+    torch.cuda.synchronize()
+    p_ref, o_ref = orc.permute(to_np(labels[0, 0]), C, 0)
+    assert np.array_equal(to_np(perm[0, 0]), p_ref) and np.array_equal(to_np(off[0, 0]), o_ref)
+    X = torch.randn(1, 1, N, d, generator=g).to(torch.bfloat16).to(dev())
+    init = X[0, 0][torch.randperm(N, generator=g)[:C].to(dev())].float()[None, None].contiguous()
+    cent = init.clone()
+    for it in range(2):
+        before = to_np(cent[0, 0]).copy()
+        lab, cnt, _ = sv.kmeans(X, cent, 1)
+        torch.cuda.synchronize()
+        lab_ref = orc.kmeans_assign(to_np(X[0, 0]), before)
+        assert np.array_equal(to_np(lab[0, 0]), lab_ref)
+        c_ref, n_ref = orc.cluster_means(to_np(X[0, 0]), lab_ref, C, before)
+        assert np.array_equal(to_np(cnt[0, 0]), n_ref)
+        assert np.allclose(to_np(cent[0, 0]), c_ref, atol=2e-5)
