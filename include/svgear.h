@@ -192,6 +192,9 @@ int svgear_probe_route_top_p(const float* qbar, const float* kbar, const float* 
  *   q_offsets, k_offsets, mask_bits, row_ptr, col_idx as produced by svgear_probe_route
  *   op  [BH,Nq,d] dt out (permuted order);  lse [BH,Nq] fp32 out or NULL: natural log of the
  *   softmax denominator of each row.
+ * Limit of the bf16 kernels: the per-key-cluster tables sit in LDS beside the K/V tile buffers
+ * (12 bytes per key cluster), which allows Ck up to about 2500 for d = 128 and 8192 for d = 64;
+ * SVGEAR_ERR_UNSUPPORTED beyond that. fp32 has no such limit.
  */
 size_t svgear_sparse_attn_comp_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
                                          int Ck);
