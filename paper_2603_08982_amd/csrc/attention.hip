@@ -242,6 +242,7 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   const int BH = B * H;
   if ((int64_t)BH * ((int64_t)ceil_div(Nq, 64) + Cq + 1) > INT32_MAX / 2) return SVGEAR_ERR_UNSUPPORTED;
   if (part != 0 && !(dt == SVGEAR_BF16 && d == 128)) return SVGEAR_ERR_UNSUPPORTED;
+  if (dt == SVGEAR_BF16 && attn_bf16_lds_bytes(d, Ck) > 160 * 1024) return SVGEAR_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   Workspace w(ws, ws_bytes);
   const int BM = attn_bm(dt, d);
@@ -272,7 +273,6 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   SVGEAR_LAUNCH_CHECK();
   to_bf16_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(vbar, n, vbar16);
   SVGEAR_LAUNCH_CHECK();
-  if (attn_bf16_lds_bytes(d, Ck) > 160 * 1024) return SVGEAR_ERR_UNSUPPORTED;
   if (d == 128) {
     const int rc = plan_d128(a, static_cast<char*>(ws) + w.used, ws_bytes - w.used, s);
     if (rc != SVGEAR_OK) return rc;

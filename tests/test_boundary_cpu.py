@@ -75,6 +75,42 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
                                        2, 2, 0.125, fake, None, fake, big, None) == -1
 
 
+def test_argument_checks_of_the_variant_entry_points(lib):
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: argument checks come first
+    big = ctypes.c_size_t(1 << 40)
+    st = (ctypes.c_int64 * 3)(128 * 16, 128 * 16, 128)
+    F = ctypes.c_float
+    # adaptive budgets: p outside (0, 1], the per-row flag, a missing output
+    for p in (0.0, -1.0, 1.5, float("nan")):
+        assert lib.svgear_probe_route_top_p(fake, fake, fake, fake, fake, 1, fake, fake, 1, 1, 16, 16, 128, 2, 2, F(p),
+                                            F(0.1), 0, fake, fake, fake, fake, fake, fake, fake, big, None) == -1
+    assert lib.svgear_probe_route_top_p(fake, fake, fake, fake, fake, 1, fake, fake, 1, 1, 16, 16, 128, 2, 2, F(0.5),
+                                        F(0.1), 2, fake, fake, fake, fake, fake, fake, fake, big, None) == -1
+    assert lib.svgear_probe_route_top_p(fake, fake, fake, fake, fake, 1, fake, fake, 1, 1, 16, 16, 128, 2, 2, F(0.5),
+                                        F(0.1), 0, fake, fake, fake, fake, fake, None, fake, big, None) == -1
+    # row movement alone: no tensors, a null permutation
+    src = (ctypes.c_void_p * 1)(0x1000)
+    sst = ((ctypes.c_int64 * 3) * 1)((128 * 16, 128 * 16, 128))
+    assert lib.svgear_permute_rows(fake, 1, 1, 16, 0, src, sst, src, 1, 128, None) == -1
+    assert lib.svgear_permute_rows(None, 1, 1, 16, 1, src, sst, src, 1, 128, None) == -1
+    # token-order attention: missing permutation, rows that are not 16-byte aligned, stride_n < d
+    args_tail = (1, 1, 16, 16, 128, 2, 2, F(0.1))
+    assert lib.svgear_sparse_attn_comp_token_order(fake, st, fake, fake, 1, fake, fake, fake, fake, fake, fake, fake,
+                                                   None, *args_tail, fake, st, None, fake, big, None) == -1
+    bad = (ctypes.c_int64 * 3)(129 * 16, 129 * 16, 129)
+    assert lib.svgear_sparse_attn_comp_token_order(fake, st, fake, fake, 1, fake, fake, fake, fake, fake, fake, fake,
+                                                   fake, *args_tail, fake, bad, None, fake, big, None) == -1
+    short = (ctypes.c_int64 * 3)(64 * 16, 64 * 16, 64)
+    assert lib.svgear_sparse_attn_comp_token_order(fake, short, fake, fake, 1, fake, fake, fake, fake, fake, fake,
+                                                   fake, fake, *args_tail, fake, st, None, fake, big, None) == -1
+    # more key clusters than the bf16 kernels' LDS tables hold: refused before anything is launched
+    assert lib.svgear_sparse_attn_comp(fake, fake, fake, 1, fake, fake, fake, fake, fake, fake, fake, 1, 1, 4096, 4096,
+                                       128, 2, 3000, F(0.1), fake, None, fake, big, None) == -4
+    # the two-stage form exists for bf16, d = 128 only
+    assert lib.svgear_sparse_attn_two_stage(fake, fake, fake, 0, fake, fake, fake, fake, fake, fake, fake, 1, 1, 16, 16,
+                                            128, 2, 2, F(0.1), fake, None, fake, big, None) == -4
+
+
 def test_product_has_no_cpu_fallback():
     import torch
 
