@@ -26,7 +26,19 @@ def _run_full(name, iters, top_p=None):
     return wl, Q, K, V, cq0, ck0, O, r, budget
 
 
-@pytest.mark.parametrize("name,top_p", [("wan", None), ("hunyuan", None), ("wan_c300", None), ("wan_c300", 0.85)])
+def _printed_top_p():
+    """TopP of the method's Wan2.2 row in the paper's hyper-parameter table (tests/golden/)."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "hyperparameters_svg_ear.txt")
+    for line in open(path):
+        f = line.split("#")[0].split()
+        if f and f[0] == "wan2.2_a14b_720p" and f[1] == "full":
+            return float(f[4])
+    raise AssertionError("fixture row missing")
+
+
+@pytest.mark.parametrize("name,top_p", [("wan", None), ("hunyuan", None), ("wan_c300", None),
+                                        ("wan_c300", _printed_top_p())])
 def test_full_size_layer_sampled_parity(name, top_p):
     """top_p = None: one budget per head; 0.85 with 300/1000 clusters: the adaptive
     per-query-cluster budgets at the cluster counts and TopP of the paper's Wan2.2 row
