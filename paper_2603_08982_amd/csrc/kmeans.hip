@@ -50,27 +50,46 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
   const int64_t n = (int64_t)Cpad * d;
   if (amb_count && blockIdx.x == 0 && threadIdx.x == 0) amb_count[bh] = 0;
   if (act_count && blockIdx.x == 0 && threadIdx.x == 0) act_count[bh] = 0;
+  // both operand tables are written 16 bytes per thread from 32 contiguous bytes of a centroid row
   if (chl) {
     const int ksn = d / 16;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-      const int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
-      const int64_t rest = i >> 9;  // blk * ksn + s
+    for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n / 8; u += (int64_t)gridDim.x * 256) {
+      const int lane = (int)(u & 63);
+      const int64_t rest = u >> 6;  // blk * ksn + s
       const int sidx = (int)(rest % ksn), blk = (int)(rest / ksn);
-      const int c = 32 * blk + (lane & 31), k = 16 * sidx + 8 * (lane >> 5) + e;
-      const float v = c < C ? cb[(int64_t)c * d + k] : 0.f;
-      const bf16_t hi = f32_to_bf16(v);
-      const bf16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
-      const int64_t base = (int64_t)bh * 2 * n + (((int64_t)blk * 2) * ksn + sidx) * 512 + lane * 8 + e;
-      chl[base] = hi;
-      chl[base + (int64_t)ksn * 512] = lo;
+      const int c = 32 * blk + (lane & 31), k0 = 16 * sidx + 8 * (lane >> 5);
+      float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (c < C) {
+        const float4* src = reinterpret_cast<const float4*>(cb + (int64_t)c * d + k0);
+        const float4 v0 = src[0], v1 = src[1];
+        v[0] = v0.x; v[1] = v0.y; v[2] = v0.z; v[3] = v0.w;
+        v[4] = v1.x; v[5] = v1.y; v[6] = v1.z; v[7] = v1.w;
+      }
+      uint32_t hw[4], lw[4];
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const bf16_t h0 = f32_to_bf16(v[e]), h1 = f32_to_bf16(v[e + 1]);
+        const bf16_t l0 = f32_to_bf16(v[e] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[e + 1] - bf16_to_f32(h1));
+        hw[e >> 1] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        lw[e >> 1] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+      }
+      const int64_t base = (int64_t)bh * 2 * n + (((int64_t)blk * 2) * ksn + sidx) * 512 + lane * 8;
+      *reinterpret_cast<uint4*>(chl + base) = uint4{hw[0], hw[1], hw[2], hw[3]};
+      *reinterpret_cast<uint4*>(chl + base + (int64_t)ksn * 512) = uint4{lw[0], lw[1], lw[2], lw[3]};
     }
   }
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int j = (int)(i & 3), lane = (int)((i >> 2) & 63);
-    const int64_t rest = i >> 8;  // blk * (d/8) + q
+  for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n / 4; u += (int64_t)gridDim.x * 256) {
+    const int lane = (int)(u & 63);
+    const int64_t rest = u >> 6;  // blk * (d/8) + q
     const int q = (int)(rest % (d / 8)), blk = (int)(rest / (d / 8));
-    const int c = 32 * blk + (lane & 31), k = 2 * (4 * q + j) + (lane >> 5);
-    cperm[(int64_t)bh * n + i] = c < C ? cb[(int64_t)c * d + k] : 0.f;
+    const int c = 32 * blk + (lane & 31), h = lane >> 5;
+    float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < C) {  // dims 8q + 2j + h, j = 0..3
+      const float4* src = reinterpret_cast<const float4*>(cb + (int64_t)c * d + 8 * q);
+      const float4 v0 = src[0], v1 = src[1];
+      out = h ? make_float4(v0.y, v0.w, v1.y, v1.w) : make_float4(v0.x, v0.z, v1.x, v1.z);
+    }
+    *reinterpret_cast<float4*>(cperm + (int64_t)bh * n + u * 4) = out;
   }
   for (int c = blockIdx.x * 256 + threadIdx.x; c < Cpad; c += gridDim.x * 256) {
     if (dirty) dirty[(int64_t)bh * Cpad + c] = 0;  // no cluster has gained or lost a member yet
