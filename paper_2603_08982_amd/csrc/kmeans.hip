@@ -284,42 +284,6 @@ constexpr int kFilterCopyWaves = 32 % kFilterWaves == 0 ? kFilterWaves : 4;
 constexpr int kFilterRowsPerWave = 64;  // two 32-row operand sets share every centroid fragment
 constexpr int kFilterRows = kFilterWaves * kFilterRowsPerWave;
 
-// |x|_2 of every row (fp32), once per call: the input does not change between iterations.
-// D/8 lanes share a row (16 bytes each, so a wave's load covers whole rows back to back), four
-// rows per lane group in flight.
-constexpr int kNormPasses = 4;
-template <int D>
-__global__ void __launch_bounds__(256)
-row_norm_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, float* __restrict__ xnorm) {
-  constexpr int LPR = D / 8;      // lanes per row
-  constexpr int RPP = 256 / LPR;  // rows per pass of the workgroup
-  const int bh = blockIdx.y, sub = threadIdx.x / LPR, lane = threadIdx.x % LPR;
-  const int64_t row0 = (int64_t)blockIdx.x * (RPP * kNormPasses) + sub;
-  const bf16_t* xb = x + head_base(st, bh, H) + lane * 8;
-  uint4 raw[kNormPasses];
-#pragma unroll
-  for (int p = 0; p < kNormPasses; ++p) {
-    const int64_t row = row0 + p * RPP;
-    raw[p] = row < nv ? *reinterpret_cast<const uint4*>(xb + row * st.n) : uint4{0u, 0u, 0u, 0u};
-  }
-#pragma unroll
-  for (int p = 0; p < kNormPasses; ++p) {
-    const uint32_t w[4] = {raw[p].x, raw[p].y, raw[p].z, raw[p].w};
-    float acc = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
-      acc = __builtin_fmaf(lo, lo, acc);
-      acc = __builtin_fmaf(hi, hi, acc);
-    }
-#pragma unroll
-    for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    const int64_t row = row0 + p * RPP;
-    // upper bound (an fp32 sum of d squares, in any order, is within d 2^-24 of the exact one)
-    if (lane == 0 && row < nv) xnorm[(int64_t)bh * nv + row] = sqrtf(acc) * 1.00002f;
-  }
-}
-
 // How far every centroid moved since the previous call, |c - c_prev| rounded up, and
 // c_prev = c for the next one. One workgroup of D threads per centroid, fixed-order sum.
 template <int D>
@@ -366,7 +330,7 @@ __device__ __forceinline__ float fixed_order_error(float X, float Cm) {
 template <int D>
 __global__ void __launch_bounds__(64 * kFilterWaves)
 assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, const bf16_t* __restrict__ chl,
-                     const float* __restrict__ cn, const float* __restrict__ xnorm, int C, int Cpad,
+                     const float* __restrict__ cn, float* __restrict__ xnorm, int C, int Cpad,
                      int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
                      const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
                      float* __restrict__ ub, float* __restrict__ lb, int32_t* __restrict__ dirty) {
@@ -416,6 +380,34 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
     for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(*reinterpret_cast<const uint4*>(xr + 16 * s + 8 * lh));
   }
   SVGEAR_WAIT_VMCNT(0);
+  // |x|_2 of the rows, rounded up: the first pass (every row, no row list) computes it from the
+  // operands it holds - each lane squares its half of the row, the halves meet across lane^32 -
+  // and stores it for the later passes and the bounds; an fp32 sum of d squares in any order
+  // is within d 2^-24 of the exact one, which the factor covers
+  float xn[2];
+#pragma unroll
+  for (int rs = 0; rs < 2; ++rs) {
+    if (row_list) {
+      xn[rs] = xnorm[(int64_t)bh * nv + rows[rs]];
+    } else {
+      float acc = 0.f;
+#pragma unroll
+      for (int s = 0; s < KSN; ++s) {
+        union { bf16x8 b; uint4 u; } c;
+        c.b = bx[rs][s];
+        const uint32_t w[4] = {c.u.x, c.u.y, c.u.z, c.u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+          acc = __builtin_fmaf(lo, lo, acc);
+          acc = __builtin_fmaf(hi, hi, acc);
+        }
+      }
+      acc += __shfl_xor(acc, 32);
+      xn[rs] = sqrtf(acc) * 1.00002f;
+      if (lh == 0 && valid[rs]) xnorm[(int64_t)bh * nv + rows[rs]] = xn[rs];
+    }
+  }
 
   const unsigned char* cp = reinterpret_cast<const unsigned char*>(chl + (int64_t)bh * 2 * Cpad * D);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -516,7 +508,7 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
     const float sec = fminf(hi, fminf(second[rs], os));
     const int a = (ob < best[rs] || (ob == best[rs] && oa < arg[rs])) ? oa : arg[rs];
     if (lh == 0 && valid[rs]) {
-      const float X = xnorm[(int64_t)bh * nv + rows[rs]];
+      const float X = xn[rs];
       const float B = 2.0f * X * Cm * kappa + 1.1920928955078125e-07f * (Cm * Cm + 2.0f * X * Cm);
       if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
         const int cur = labels[(int64_t)bh * nv + rows[rs]];
@@ -795,9 +787,6 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   if constexpr (kFilter) {
     SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
-    row_norm_kernel<D><<<dim3((unsigned)ceil_div(nv, (256 / (D / 8)) * kNormPasses), BH), 256, 0, s>>>(
-        reinterpret_cast<const bf16_t*>(x), st, H, nv, xnorm);
-    SVGEAR_LAUNCH_CHECK();
   }
   const dim3 gp((unsigned)ceil_div((int64_t)Cpad * D, 256 * 4), BH);
   const dim3 ga((unsigned)ceil_div(nv, kAssignRows), BH);
