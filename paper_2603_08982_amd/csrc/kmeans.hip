@@ -548,13 +548,15 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
 constexpr int kBoundRows = 8;  // rows per thread of bounds_update_kernel
 
 // Per head: Cm^2 = max |c|^2, the largest and second largest centroid move, and whose the
-// largest is (stats[bh] = {Cm^2, d1, d2, a1 as float bits}); one workgroup per head.
-__global__ void __launch_bounds__(256)
-head_stats_kernel(const float* __restrict__ cn, const float* __restrict__ drift, int C, int Cpad,
-                  float* __restrict__ stats) {
+// largest is. Every workgroup of bounds_update_kernel works them out for itself from the
+// per-centroid tables (a few hundred loads; a kernel of its own cost a launch per iteration).
+// Called by all 256 threads; the same code on the same tables gives every workgroup the same
+// answer, also among equal moves.
+__device__ __forceinline__ void head_stats(const float* __restrict__ cn, const float* __restrict__ drift, int C,
+                                           float& cm2_out, float& d1_out, float& d2_out, int& a1_out) {
   __shared__ float s_cm2[4], s_d1[4], s_d2[4];
   __shared__ int s_a1[4];
-  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float cm2 = 0.f, d1 = 0.f, d2 = 0.f;
   int a1 = -1;
   // (d1, a1, d2) of two disjoint sets of centroids -> of their union
@@ -568,8 +570,8 @@ head_stats_kernel(const float* __restrict__ cn, const float* __restrict__ drift,
     }
   };
   for (int c = tid; c < C; c += 256) {
-    cm2 = fmaxf(cm2, cn[(int64_t)bh * Cpad + c]);
-    merge(drift[(int64_t)bh * Cpad + c], c, 0.f);
+    cm2 = fmaxf(cm2, cn[c]);
+    merge(drift[c], c, 0.f);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -580,17 +582,12 @@ head_stats_kernel(const float* __restrict__ cn, const float* __restrict__ drift,
   }
   if (lane == 0) { s_cm2[wave] = cm2; s_d1[wave] = d1; s_d2[wave] = d2; s_a1[wave] = a1; }
   __syncthreads();
-  if (tid == 0) {
-    cm2 = s_cm2[0]; d1 = s_d1[0]; d2 = s_d2[0]; a1 = s_a1[0];
-    for (int w = 1; w < 4; ++w) {
-      cm2 = fmaxf(cm2, s_cm2[w]);
-      merge(s_d1[w], s_a1[w], s_d2[w]);
-    }
-    stats[4 * bh + 0] = cm2;
-    stats[4 * bh + 1] = d1;
-    stats[4 * bh + 2] = d2;
-    stats[4 * bh + 3] = __int_as_float(a1);
+  cm2 = s_cm2[0]; d1 = s_d1[0]; d2 = s_d2[0]; a1 = s_a1[0];
+  for (int w = 1; w < 4; ++w) {
+    cm2 = fmaxf(cm2, s_cm2[w]);
+    merge(s_d1[w], s_a1[w], s_d2[w]);
   }
+  cm2_out = cm2; d1_out = d1; d2_out = d2; a1_out = a1;
 }
 
 // Which rows need a new assignment (Hamerly's bounds). ub[row] bounds the distance of the row
@@ -605,13 +602,14 @@ head_stats_kernel(const float* __restrict__ cn, const float* __restrict__ drift,
 template <int D>
 __global__ void __launch_bounds__(256)
 bounds_update_kernel(const int32_t* __restrict__ labels, const float* __restrict__ xnorm,
-                     const float* __restrict__ stats, const float* __restrict__ drift, int Cpad, int64_t nv,
+                     const float* __restrict__ cn, const float* __restrict__ drift, int C, int Cpad, int64_t nv,
                      float* __restrict__ ub, float* __restrict__ lb, int32_t* __restrict__ act_rows,
                      int32_t* __restrict__ act_count) {
   const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float Cm = sqrtf(stats[4 * bh + 0]) * 1.00002f;
-  const float d1 = stats[4 * bh + 1], d2 = stats[4 * bh + 2];
-  const int a1 = __float_as_int(stats[4 * bh + 3]);
+  float cm2, d1, d2;
+  int a1;
+  head_stats(cn + (int64_t)bh * Cpad, drift + (int64_t)bh * Cpad, C, cm2, d1, d2, a1);
+  const float Cm = sqrtf(cm2) * 1.00002f;
 
   // kBoundRows rows per thread, 256 apart (a launch of one-row threads is bound by the rate at
   // which workgroups start, not by memory)
@@ -776,7 +774,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   int32_t* act_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
   float* cent_prev = kFilter ? ws.take<float>((size_t)BH * C * D) : nullptr;
   float* drift = kFilter ? ws.take<float>((size_t)BH * Cpad) : nullptr;
-  float* stats = kFilter ? ws.take<float>((size_t)BH * 4) : nullptr;
+  if (kFilter) ws.take<float>((size_t)BH * 4);  // (reserved)
   int32_t* dirty = kFilter ? ws.take<int32_t>((size_t)BH * Cpad) : nullptr;
   if (!ws.ok()) return SVGEAR_ERR_WORKSPACE;
   const size_t lds = 2 * (size_t)kCentChunk * D * 4 + 2 * kCentChunk * sizeof(float);
@@ -812,10 +810,8 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
       // first iteration: every row; later ones: only the rows whose bounds do not prove that
       // their label stays
       if (it > 0) {
-        head_stats_kernel<<<BH, 256, 0, s>>>(cn, drift, C, Cpad, stats);
-        SVGEAR_LAUNCH_CHECK();
         bounds_update_kernel<D><<<dim3((unsigned)ceil_div(nv, 256 * kBoundRows), BH), 256, 0, s>>>(
-            labels, xnorm, stats, drift, Cpad, nv, ub, lb, act_rows, act_count);
+            labels, xnorm, cn, drift, C, Cpad, nv, ub, lb, act_rows, act_count);
         SVGEAR_LAUNCH_CHECK();
       }
       assign_filter_kernel<D><<<dim3((unsigned)ceil_div(nv, kFilterRows), BH), 64 * kFilterWaves, lds_f, s>>>(
