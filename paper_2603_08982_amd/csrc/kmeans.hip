@@ -284,31 +284,6 @@ constexpr int kFilterCopyWaves = 32 % kFilterWaves == 0 ? kFilterWaves : 4;
 constexpr int kFilterRowsPerWave = 64;  // two 32-row operand sets share every centroid fragment
 constexpr int kFilterRows = kFilterWaves * kFilterRowsPerWave;
 
-// How far every centroid moved since the previous call, |c - c_prev| rounded up, and
-// c_prev = c for the next one. One workgroup of D threads per centroid, fixed-order sum.
-template <int D>
-__global__ void __launch_bounds__(D)
-drift_kernel(const float* __restrict__ cent, int C, int Cpad, float* __restrict__ cent_prev,
-             float* __restrict__ drift) {
-  __shared__ float part[D / 64];
-  const int c = blockIdx.x, bh = blockIdx.y, k = threadIdx.x;
-  const int64_t i = ((int64_t)bh * C + c) * D + k;
-  const float v = cent[i], dv = v - cent_prev[i];
-  cent_prev[i] = v;
-  float s = dv * dv;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-  if ((k & 63) == 0) part[k >> 6] = s;
-  __syncthreads();
-  if (k == 0) {
-    float t = part[0];
-#pragma unroll
-    for (int w = 1; w < D / 64; ++w) t += part[w];
-    // upper bound (fp32 sum of D non-negative terms: relative error below D 2^-23)
-    drift[(int64_t)bh * Cpad + c] = sqrtf(t) * 1.0001f;
-  }
-}
-
 // Distance of a fixed-order fp32 score fma(-2, x.c, |c|^2) (both sums fmaf chains over d
 // terms) from the real number |c|^2 - 2 x.c, for |x| <= X and |c| <= Cm: d 2^-24 relative on
 // each chain plus the final rounding, with head room.
@@ -665,14 +640,17 @@ __global__ void __launch_bounds__(256)
 means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restrict__ perm, int64_t N,
              const int32_t* __restrict__ offsets, int C, float* __restrict__ cent,
              int32_t* __restrict__ counts, float* __restrict__ partial, const int32_t* __restrict__ dirty,
-             int Cpad) {
+             int Cpad, float* __restrict__ drift) {
   constexpr int VEC = 16 / sizeof(T);  // elements per lane
   constexpr int LPR = D / VEC;         // lanes per row
   constexpr int SLOTS = 256 / LPR;
   __shared__ float red[SLOTS][D];
   const int c = blockIdx.x, bh = blockIdx.y;
   // a cluster whose membership did not change keeps its centroid and count (same sum)
-  if (dirty && !dirty[(int64_t)bh * Cpad + c]) return;
+  if (dirty && !dirty[(int64_t)bh * Cpad + c]) {
+    if (drift && gridDim.z == 1 && threadIdx.x == 0) drift[(int64_t)bh * Cpad + c] = 0.f;  // it did not move
+    return;
+  }
   const int slot = threadIdx.x / LPR, lane = threadIdx.x % LPR;
   const int32_t* off = offsets + (int64_t)bh * (C + 2);
   const int c_start = off[c], c_end = off[c + 1];
@@ -712,36 +690,84 @@ means_kernel(const T* __restrict__ x, Strides st, int H, const int32_t* __restri
   for (int k = 0; k < VEC; ++k) red[slot][lane * VEC + k] = acc[k];
   __syncthreads();
   const int cnt = c_end - c_start;
+  float dv2 = 0.f;  // this dimension's share of the centroid's squared move
   if (threadIdx.x < D && (cnt > 0 || P > 1)) {
     float s = red[0][threadIdx.x];
 #pragma unroll
     for (int k = 1; k < SLOTS; ++k) s += red[k][threadIdx.x];
-    if (P == 1) cent[((int64_t)bh * C + c) * D + threadIdx.x] = s / (float)cnt;
-    else partial[(((int64_t)bh * C + c) * P + part) * D + threadIdx.x] = s;
+    if (P == 1) {
+      const int64_t ci = ((int64_t)bh * C + c) * D + threadIdx.x;
+      const float v = s / (float)cnt;
+      if (drift) {
+        const float dv = v - cent[ci];
+        dv2 = dv * dv;
+      }
+      cent[ci] = v;
+    } else {
+      partial[(((int64_t)bh * C + c) * P + part) * D + threadIdx.x] = s;
+    }
   }
   if (P == 1 && threadIdx.x == 0 && counts) counts[(int64_t)bh * C + c] = cnt;
+  if (P == 1 && drift) {
+    // how far the centroid moved, rounded up (an fp32 sum of D non-negative terms is within
+    // D 2^-23 of the exact one): the row bounds of the next iteration need it
+    __shared__ float dpart[D / 64];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) dv2 += __shfl_xor(dv2, o);
+    if (threadIdx.x < D && (threadIdx.x & 63) == 0) dpart[threadIdx.x >> 6] = dv2;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float t = dpart[0];
+#pragma unroll
+      for (int w = 1; w < D / 64; ++w) t += dpart[w];
+      drift[(int64_t)bh * Cpad + c] = sqrtf(t) * 1.0001f;
+    }
+  }
 }
 
 // Adds the P partial sums of every cluster in part order and divides by the member count; a
-// cluster without members keeps its centroid.
+// cluster without members keeps its centroid. With drift != nullptr it also records how far
+// every centroid moved (rounded up; 0 for the clusters that were not touched). D is 64 or 128,
+// so the D threads of a centroid are whole waves of one workgroup.
 __global__ void __launch_bounds__(256)
 means_finish_kernel(const float* __restrict__ partial, const int32_t* __restrict__ offsets, int C, int P, int D,
                     float* __restrict__ cent, int32_t* __restrict__ counts, const int32_t* __restrict__ dirty,
-                    int Cpad) {
+                    int Cpad, float* __restrict__ drift) {
+  __shared__ float dpart[4];
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (bh, c, dim)
   const int bh = blockIdx.y;
-  if (i >= (int64_t)C * D) return;
-  const int c = (int)(i / D), dim = (int)(i % D);
-  if (dirty && !dirty[(int64_t)bh * Cpad + c]) return;
-  const int32_t* off = offsets + (int64_t)bh * (C + 2);
-  const int cnt = off[c + 1] - off[c];
-  if (cnt > 0) {
-    const float* pp = partial + (((int64_t)bh * C + c) * P) * D + dim;
-    float s = pp[0];
-    for (int k = 1; k < P; ++k) s += pp[(int64_t)k * D];
-    cent[((int64_t)bh * C + c) * D + dim] = s / (float)cnt;
+  const bool in = i < (int64_t)C * D;
+  const int c = in ? (int)(i / D) : 0, dim = in ? (int)(i % D) : 1;
+  float dv2 = 0.f;
+  if (in && !(dirty && !dirty[(int64_t)bh * Cpad + c])) {
+    const int32_t* off = offsets + (int64_t)bh * (C + 2);
+    const int cnt = off[c + 1] - off[c];
+    if (cnt > 0) {
+      const float* pp = partial + (((int64_t)bh * C + c) * P) * D + dim;
+      float s = pp[0];
+      for (int k = 1; k < P; ++k) s += pp[(int64_t)k * D];
+      const int64_t ci = ((int64_t)bh * C + c) * D + dim;
+      const float v = s / (float)cnt;
+      if (drift) {
+        const float dv = v - cent[ci];
+        dv2 = dv * dv;
+      }
+      cent[ci] = v;
+    }
+    if (dim == 0 && counts) counts[(int64_t)bh * C + c] = cnt;
   }
-  if (dim == 0 && counts) counts[(int64_t)bh * C + c] = cnt;
+  if (drift) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) dv2 += __shfl_xor(dv2, o);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) dpart[wave] = dv2;
+    __syncthreads();
+    if (in && dim == 0) {
+      float t = dpart[wave];
+      for (int w = 1; w < D / 64; ++w) t += dpart[wave + w];
+      drift[(int64_t)bh * Cpad + c] = sqrtf(t) * 1.0001f;
+    }
+  }
 }
 
 // Parts per cluster of the centroid update: about 128 members per part on average, at most 8.
@@ -772,7 +798,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   float* lb = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
   int32_t* act_rows = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
   int32_t* act_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
-  float* cent_prev = kFilter ? ws.take<float>((size_t)BH * C * D) : nullptr;
+  if (kFilter) ws.take<float>((size_t)BH * C * D);  // (reserved)
   float* drift = kFilter ? ws.take<float>((size_t)BH * Cpad) : nullptr;
   if (kFilter) ws.take<float>((size_t)BH * 4);  // (reserved)
   int32_t* dirty = kFilter ? ws.take<int32_t>((size_t)BH * Cpad) : nullptr;
@@ -790,21 +816,20 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   const dim3 ga((unsigned)ceil_div(nv, kAssignRows), BH);
   // only_changed: clusters that neither gained nor lost a member in this iteration keep their
   // centroid (flags set by the assignment kernels; null = every cluster)
-  auto update = [&](const T* src, float* dst, int32_t* cnt_out, const int32_t* only_changed) -> int {
+  // moves: where the update records how far every centroid moved (null = not needed)
+  auto update = [&](const T* src, float* dst, int32_t* cnt_out, const int32_t* only_changed, float* moves) -> int {
     means_kernel<T, D><<<dim3(C, BH, P), 256, 0, s>>>(src, st, H, perm, nv, offsets, C, dst, cnt_out, partial,
-                                                      only_changed, Cpad);
+                                                      only_changed, Cpad, moves);
     SVGEAR_LAUNCH_CHECK();
     if (P > 1) {
       means_finish_kernel<<<dim3((unsigned)ceil_div((int64_t)C * D, 256), BH), 256, 0, s>>>(
-          partial, offsets, C, P, D, dst, cnt_out, only_changed, Cpad);
+          partial, offsets, C, P, D, dst, cnt_out, only_changed, Cpad, moves);
       SVGEAR_LAUNCH_CHECK();
     }
     return SVGEAR_OK;
   };
   for (int it = 0; it < iters; ++it) {
     prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count, act_count, dirty);
-    SVGEAR_LAUNCH_CHECK();
-    if constexpr (kFilter) drift_kernel<D><<<dim3(C, BH), D, 0, s>>>(cent, C, Cpad, cent_prev, drift);
     SVGEAR_LAUNCH_CHECK();
     if constexpr (kFilter) {
       // first iteration: every row; later ones: only the rows whose bounds do not prove that
@@ -826,11 +851,11 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
     SVGEAR_LAUNCH_CHECK();
     int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s);
     if (rc != SVGEAR_OK) return rc;
-    rc = update(x, cent, counts, (kFilter && it > 0) ? dirty : nullptr);
+    rc = update(x, cent, counts, (kFilter && it > 0) ? dirty : nullptr, drift);
     if (rc != SVGEAR_OK) return rc;
   }
   if (x2) {
-    const int rc = update(x2, cent2, nullptr, nullptr);
+    const int rc = update(x2, cent2, nullptr, nullptr, nullptr);
     if (rc != SVGEAR_OK) return rc;
   }
   return SVGEAR_OK;
