@@ -52,9 +52,13 @@ plan_kernel(const int32_t* __restrict__ q_offsets, int Cq, int BM, int max_tiles
   }
 }
 
-__global__ void to_bf16_kernel(const float* __restrict__ src, int64_t n, bf16_t* __restrict__ dst) {
+// Both centroid tables to bf16 in one launch (blockIdx.y picks the table).
+__global__ void to_bf16_kernel(const float* __restrict__ src0, const float* __restrict__ src1, int64_t n,
+                               bf16_t* __restrict__ dst0, bf16_t* __restrict__ dst1) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = f32_to_bf16(src[i]);
+  if (i >= n) return;
+  if (blockIdx.y == 0) dst0[i] = f32_to_bf16(src0[i]);
+  else dst1[i] = f32_to_bf16(src1[i]);
 }
 
 // ------------------------------------------------------------------------------ fp32
@@ -254,8 +258,10 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   bf16_t* kbar16 = w.take<bf16_t>((size_t)BH * Ck * d);
   bf16_t* vbar16 = w.take<bf16_t>((size_t)BH * Ck * d);
   if (!w.ok()) return SVGEAR_ERR_WORKSPACE;
-  plan_kernel<<<BH, 256, (Cq + 2) * sizeof(int32_t), s>>>(q_offsets, Cq, BM, max_tiles, tile_a, tile_row0, n_tiles);
-  SVGEAR_LAUNCH_CHECK();
+  if (!(dt == SVGEAR_BF16 && d == 128)) {  // the d = 128 bf16 kernel has work lists of its own (plan_d128)
+    plan_kernel<<<BH, 256, (Cq + 2) * sizeof(int32_t), s>>>(q_offsets, Cq, BM, max_tiles, tile_a, tile_row0, n_tiles);
+    SVGEAR_LAUNCH_CHECK();
+  }
   AttnArgs a{qp, kp, vp, kbar, vbar, kbar16, vbar16, q_offsets, k_offsets, mask_bits, row_ptr, col_idx,
              tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr,
              Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part, tok_perm, q_st, out_st, H};
@@ -269,9 +275,7 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
     return SVGEAR_OK;
   }
   const int64_t n = (int64_t)BH * Ck * d;
-  to_bf16_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(kbar, n, kbar16);
-  SVGEAR_LAUNCH_CHECK();
-  to_bf16_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(vbar, n, vbar16);
+  to_bf16_kernel<<<dim3((unsigned)ceil_div(n, 256), 2), 256, 0, s>>>(kbar, vbar, n, kbar16, vbar16);
   SVGEAR_LAUNCH_CHECK();
   if (d == 128) {
     const int rc = plan_d128(a, static_cast<char*>(ws) + w.used, ws_bytes - w.used, s);
