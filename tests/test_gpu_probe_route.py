@@ -210,3 +210,43 @@ def test_route_with_thousands_of_key_clusters():
     m_ref, _, _, cost_ref = orc.route(to_np(scores[0, 0]), q_sizes, k_sizes, 0, row_budgets=got)
     assert np.array_equal(bits_to_mask(to_np(t["mask_bits"][0, 0]), Ck), full_mask(m_ref, Cq, Ck))
     assert int(t["routed_cost"][0, 0]) == cost_ref
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_adaptive_budgets_with_empty_clusters_and_tail(d):
+    """Empty query and key clusters (budget 0 / never kept) and a text tail (its column comes on top
+    of the row budgets), from injected scores."""
+    rng = np.random.default_rng(17)
+    Cq, Ck, nv, n_tail = 7, 23, 900, 19
+    N = nv + n_tail
+    lab_q = rng.integers(0, Cq, nv).astype(np.int32)
+    lab_q[lab_q == 2] = 3                      # query cluster 2 is empty
+    lab_k = rng.integers(0, Ck, nv).astype(np.int32)
+    lab_k[(lab_k == 0) | (lab_k == 11) | (lab_k == Ck - 1)] = 5  # three empty key clusters
+    tq = torch.from_numpy(lab_q)[None, None].to(dev())
+    tk = torch.from_numpy(lab_k)[None, None].to(dev())
+    _, qoff, _ = sv.permute(tq, Cq, n_tail=n_tail)
+    _, koff, _ = sv.permute(tk, Ck, n_tail=n_tail)
+    qbar = torch.from_numpy(rng.standard_normal((1, 1, Cq, d)).astype(np.float32)).to(dev())
+    kbar = torch.from_numpy(rng.standard_normal((1, 1, Ck, d)).astype(np.float32)).to(dev())
+    vbar = torch.zeros_like(kbar)
+    Kp = torch.zeros(1, 1, N, d, dtype=torch.bfloat16, device=dev())
+    scores = torch.from_numpy(rng.random((1, 1, Cq, Ck)).astype(np.float32)).to(dev())
+    q_sizes = np.bincount(lab_q, minlength=Cq)
+    k_sizes = np.bincount(lab_k, minlength=Ck)
+    scale = orc.scale_of(d)
+    for p in (0.2, 0.6, 1.0):
+        t = sv.probe_route(qbar, kbar, vbar, Kp, Kp, qoff, koff, 0, scale, flags=sv.USE_GIVEN_SCORES,
+                           scores=scores.clone(), top_p=p)
+        torch.cuda.synchronize()
+        got = to_np(t["row_budget"][0, 0])
+        assert got[2] == 0
+        ref_head = dict(qbar=to_np(qbar[0, 0]), kbar=to_np(kbar[0, 0]), qcnt=q_sizes, kcnt=k_sizes)
+        _check_row_budgets(got, ref_head, None, p, scale)
+        m_ref, _, _, cost_ref = orc.route(to_np(scores[0, 0]), q_sizes, k_sizes, 0, n_tail_q=n_tail, n_tail_k=n_tail,
+                                          row_budgets=got)
+        mask = bits_to_mask(to_np(t["mask_bits"][0, 0]), Ck)
+        assert np.array_equal(mask, full_mask(m_ref, Cq, Ck))
+        assert not mask[2].any() and not mask[:, [0, 11, Ck - 1]].any()
+        assert mask[[0, 1, 3, 4, 5, 6], Ck].all() and mask[Cq, np.nonzero(k_sizes)[0]].all()
+        assert int(t["routed_cost"][0, 0]) == cost_ref
