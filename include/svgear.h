@@ -109,6 +109,25 @@ int svgear_permute(const int32_t* labels, int B, int H, int64_t N, int64_t n_tai
                    void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * svgear_permute for callers that cannot allocate device memory and so have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc. The sort's scratch (per-chunk label histograms) is a fixed array inside the
+ * library's device image (svgear_permute_static_capacity() bytes, 8 MiB, held on every GPU
+ * the library runs on until the process ends) instead of `ws`; the call allocates and frees
+ * nothing. Arguments and results are exactly those of svgear_permute.
+ *   - SVGEAR_ERR_WORKSPACE if svgear_permute_workspace(B, H, N, C) exceeds the capacity
+ *     (e.g. B*H*ceil(N/2048)*(C+1) counters of 4 bytes: 40 heads x 75,600 tokens x C <= 1416).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (different streams or threads) race. Calls on one stream are ordered and safe; nothing
+ *     has to be cleared between them (every counter is written before it is read).
+ */
+size_t svgear_permute_static_capacity(void);
+int svgear_permute_static(const int32_t* labels, int B, int H, int64_t N, int64_t n_tail, int C,
+                          int32_t* perm, int32_t* offsets, int n_tensors, const void* const* src,
+                          const int64_t (*sstride)[3], void* const* dst, svgear_dtype dt, int d,
+                          void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * The row movement of svgear_permute alone: dst[k][bh][p][:] = src[k][b,h,perm[p],:] for a
  * permutation already computed (svgear_permute with n_tensors = 0 returns perm and offsets
  * only). For callers that overlap the two halves with other work: the probe needs the

@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = [
     "svgear_version", "svgear_last_hip_error",
     "svgear_kmeans_workspace", "svgear_kmeans",
     "svgear_permute_workspace", "svgear_permute", "svgear_permute_rows",
+    "svgear_permute_static_capacity", "svgear_permute_static",
     "svgear_probe_route_workspace", "svgear_probe_route", "svgear_probe_route_top_p",
     "svgear_sparse_attn_comp_workspace", "svgear_sparse_attn_comp", "svgear_sparse_attn_comp_token_order",
     "svgear_sparse_attn_two_stage_workspace", "svgear_sparse_attn_two_stage",
@@ -65,6 +66,10 @@ def load_library():
     lib.svgear_permute.restype = _i
     lib.svgear_permute.argtypes = [_vp, _i, _i, _i64, _i64, _i, _vp, _vp, _i, _c.POINTER(_vp),
                                    _c.POINTER(_I64x3), _c.POINTER(_vp), _i, _i, _vp, _sz, _vp]
+    lib.svgear_permute_static_capacity.restype = _sz
+    lib.svgear_permute_static_capacity.argtypes = []
+    lib.svgear_permute_static.restype = _i
+    lib.svgear_permute_static.argtypes = lib.svgear_permute.argtypes[:14] + [_vp]
     lib.svgear_permute_rows.restype = _i
     lib.svgear_permute_rows.argtypes = [_vp, _i, _i, _i64, _i, _c.POINTER(_vp), _c.POINTER(_I64x3), _c.POINTER(_vp),
                                         _i, _i, _vp]
@@ -157,26 +162,42 @@ def kmeans(x: torch.Tensor, centroids: torch.Tensor, iters: int, n_tail: int = 0
     return labels, counts, c2
 
 
-def permute(labels: torch.Tensor, C: int, tensors: Sequence[torch.Tensor] = (), n_tail: int = 0):
-    """svgear_permute. Returns (perm [B,H,N] i32, offsets [B,H,C+2] i32, [permuted tensors])."""
+def permute(labels: torch.Tensor, C: int, tensors: Sequence[torch.Tensor] = (), n_tail: int = 0,
+            static_scratch: bool = False, out=None):
+    """svgear_permute (static_scratch=True: svgear_permute_static, whose scratch is an array inside
+    the library; with out=(perm, offsets, [dst tensors]) preallocated by the caller that call
+    touches no allocator at all). Returns (perm [B,H,N] i32, offsets [B,H,C+2] i32, [permuted tensors])."""
     _need_gpu(labels, *tensors)
     lib = load_library()
     B, H, nv = labels.shape
     N = nv + n_tail
     assert labels.dtype == torch.int32 and labels.is_contiguous()
-    perm = torch.empty(B, H, N, dtype=torch.int32, device=labels.device)
-    offsets = torch.empty(B, H, C + 2, dtype=torch.int32, device=labels.device)
     n = len(tensors)
     d, dt = 64, 0
-    outs = []
     if n:
         d, dt = tensors[0].shape[3], _dt(tensors[0])
         for t in tensors:
             assert t.shape == (B, H, N, d) and _dt(t) == dt
+    if out is not None:
+        perm, offsets, outs = out
+        assert perm.shape == (B, H, N) and perm.dtype == torch.int32 and perm.is_contiguous()
+        assert offsets.shape == (B, H, C + 2) and offsets.dtype == torch.int32 and offsets.is_contiguous()
+        assert len(outs) == n
+        for o, t in zip(outs, tensors):
+            assert o.shape == t.shape and o.dtype == t.dtype and o.is_contiguous()
+        _need_gpu(perm, offsets, *outs)
+    else:
+        perm = torch.empty(B, H, N, dtype=torch.int32, device=labels.device)
+        offsets = torch.empty(B, H, C + 2, dtype=torch.int32, device=labels.device)
         outs = [torch.empty(B, H, N, d, dtype=t.dtype, device=t.device) for t in tensors]
     src = (_vp * max(n, 1))(*[t.data_ptr() for t in tensors])
     dst = (_vp * max(n, 1))(*[t.data_ptr() for t in outs])
     sst = (_I64x3 * max(n, 1))(*[_strides4(t) for t in tensors])
+    if static_scratch:
+        rc = lib.svgear_permute_static(_ptr(labels), B, H, N, n_tail, C, _ptr(perm), _ptr(offsets), n, src, sst, dst,
+                                       dt, d, _stream())
+        _check(rc, "svgear_permute_static")
+        return perm, offsets, outs
     ws = _ws(lib.svgear_permute_workspace(B, H, N, C), labels.device)
     rc = lib.svgear_permute(_ptr(labels), B, H, N, n_tail, C, _ptr(perm), _ptr(offsets), n, src, sst, dst, dt, d,
                             _ptr(ws), ws.numel(), _stream())

@@ -7,6 +7,8 @@
 // an exclusive scan over (cluster, chunk), then a stable in-chunk ranking without atomics.
 #include "common.h"
 
+#include <mutex>
+
 namespace svgear {
 
 namespace {
@@ -252,6 +254,55 @@ extern "C" int svgear_permute(const int32_t* labels, int B, int H, int64_t N, in
   int rc = sort_labels(labels, BH, N, n_tail, C, perm, offsets, static_cast<int32_t*>(ws), s);
   if (rc != SVGEAR_OK) return rc;
   return gather_tensors(perm, BH, H, N, n_tensors, src, sstride, dst, dt, d, s);
+}
+
+// ---- the same call for callers that cannot allocate -----------------------------------------
+// The sort's chunk histograms live in a file-scope device array instead of a caller workspace.
+// In host code the array's NAME is only a stand-in for the symbol; its device address is taken
+// once per device with hipGetSymbolAddress and that address is what the kernels receive.
+namespace svgear {
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call there).
+int static_scratch(void** out) {
+  int dev = -1;
+  SVGEAR_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SVGEAR_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    SVGEAR_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SVGEAR_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SVGEAR_OK;
+}
+
+}  // namespace
+}  // namespace svgear
+
+extern "C" size_t svgear_permute_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" int svgear_permute_static(const int32_t* labels, int B, int H, int64_t N, int64_t n_tail, int C,
+                                     int32_t* perm, int32_t* offsets, int n_tensors, const void* const* src,
+                                     const int64_t (*sstride)[3], void* const* dst, svgear_dtype dt, int d,
+                                     void* stream) {
+  if (B <= 0 || H <= 0 || N <= 0 || C <= 0) return SVGEAR_ERR_INVALID;
+  if (svgear_permute_workspace(B, H, N, C) > kStaticScratchBytes) return SVGEAR_ERR_WORKSPACE;
+  void* ptr = nullptr;
+  const int rc = static_scratch(&ptr);
+  if (rc != SVGEAR_OK) return rc;
+  // every counter of the histogram area in use is written by hist_kernel before it is read,
+  // so what an earlier call left in the array does not matter
+  return svgear_permute(labels, B, H, N, n_tail, C, perm, offsets, n_tensors, src, sstride, dst, dt, d, ptr,
+                        kStaticScratchBytes, stream);
 }
 
 extern "C" int svgear_permute_rows(const int32_t* perm, int B, int H, int64_t N, int n_tensors,

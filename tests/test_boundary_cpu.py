@@ -127,3 +127,13 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.replace("no CPU", ""), f
+
+
+def test_static_scratch_entry_point_rejects_on_the_host(lib):
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: argument checks come first
+    assert lib.svgear_permute_static_capacity() == 8 << 20
+    # needs more scratch than the library's fixed array holds
+    assert lib.svgear_permute_workspace(1, 40, 75600, 1500) > lib.svgear_permute_static_capacity()
+    assert lib.svgear_permute_static(fake, 1, 40, 75600, 0, 1500, fake, fake, 0, None, None, None, 1, 128, None) == -2
+    # non-positive sizes
+    assert lib.svgear_permute_static(fake, 0, 1, 16, 0, 2, fake, fake, 0, None, None, None, 1, 128, None) == -1
