@@ -12,9 +12,10 @@ Analysis" section:
         - the "Oracle solution" of the Methodology: greedy routing by the exact per-entry
           squared errors of the relaxed objective, which needs all Nq Nk logits,
       all four at the same routed cost.
-  (b) "Effect of clustering": the clustering error delta_q^2 = max_i |q_i - qbar_i|^2
-      (Proposition 1) and the attention-map error against the number of query clusters at a
-      fixed selection.
+  (b) "Effect of clustering": the clustering error of Proposition 1,
+      delta_q^2 = (1/N_q) sum_i |q_i - qbar_i|^2 (the MEAN over the queries of the squared
+      distance to the mean of the query's cluster), and the attention-map error against the
+      number of query clusters at a fixed selection.
 
 The paper does not define the top-p rule it inherits; the reading used here (and labelled as
 such wherever its numbers are shown) is: per query cluster, key clusters in descending order
@@ -90,6 +91,13 @@ def map_mse(A, A_full) -> float:
     return float((d * d).mean())
 
 
+def clustering_error(Q, qbar, lab_q) -> float:
+    """delta_q^2 of Proposition 1: the average over all queries of |q_i - qbar_i|_2^2, qbar_i
+    the centroid of query i's cluster."""
+    dq = np.asarray(Q, np.float64) - np.asarray(qbar, np.float64)[np.asarray(lab_q)]
+    return float((dq * dq).sum(axis=1).mean())
+
+
 def cluster(wl: Workload, head: int, Cq: int, Ck: int, iters: int):
     """Q, K, V of one head (fp64) with the method's k-means (seeded init) on Q and K."""
     Q, K, V = (t.float().numpy() for t in make_head(wl, head))
@@ -134,8 +142,7 @@ def clustering_study(wl: Workload, head: int = 0, cqs=(8, 16, 32, 64, 128), p: f
         Q, K, V, qbar, lab_q, q_cnt, kbar, vbar, lab_k, k_cnt = cluster(wl, head, Cq, wl.Ck, iters)
         if A_full is None:
             A_full = dense_map(Q, K, scale)
-        dq = Q.astype(np.float64) - qbar.astype(np.float64)[lab_q]
-        delta_q2 = float((dq * dq).sum(axis=1).max())
+        delta_q2 = clustering_error(Q, qbar, lab_q)
         m_top = top_p_mask(qbar, kbar, k_cnt, p, scale)
         rows.append((Cq, delta_q2,
                      map_mse(orc.attention_map_comp(Q, K, lab_q, lab_k, kbar, m_top, scale)[0], A_full)))

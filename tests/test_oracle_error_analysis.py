@@ -67,6 +67,29 @@ def test_selection_strategies_order_as_in_the_paper():
         assert ear_comp < top_comp
 
 
+def test_clustering_error_is_the_mean_over_queries_not_the_maximum():
+    # Proposition 1: delta_q^2 = (1/N_q) sum_i |q_i - qbar_i|^2. Two clusters built by hand:
+    # cluster 0 = {(0,0), (2,0)} with mean (1,0): squared distances 1, 1;
+    # cluster 1 = {(10,0), (10,6), (10,0)} with mean (10,2): squared distances 4, 16, 4.
+    # mean = (1 + 1 + 4 + 16 + 4) / 5 = 5.2, whereas the largest is 16 and the sum 26.
+    Q = np.array([[0.0, 0.0], [10.0, 0.0], [2.0, 0.0], [10.0, 6.0], [10.0, 0.0]])
+    lab = np.array([0, 1, 0, 1, 1])
+    qbar = np.array([[1.0, 0.0], [10.0, 2.0]])
+    assert ea.clustering_error(Q, qbar, lab) == 5.2
+    # one cluster holding everything: the mean squared distance to the grand mean is the
+    # trace of the (biased) covariance matrix
+    rng = np.random.default_rng(3)
+    X = rng.normal(size=(50, 4)) * np.array([1.0, 2.0, 0.5, 3.0])
+    got = ea.clustering_error(X, X.mean(0, keepdims=True), np.zeros(50, int))
+    assert np.isclose(got, np.trace(np.cov(X.T, bias=True)), rtol=1e-12)
+    # the study reports this quantity: its rows equal k-means inertia / N_q
+    Qs, _, _, qbar_s, lab_q, _, _, _, _, _ = ea.cluster(SMALL, 0, 16, SMALL.Ck, 6)
+    row = ea.clustering_study(SMALL, cqs=(16,), iters=6)[0]
+    inertia = sum(float(((Qs[i].astype(np.float64) - qbar_s[lab_q[i]].astype(np.float64)) ** 2).sum())
+                  for i in range(Qs.shape[0]))
+    assert np.isclose(row[1], inertia / Qs.shape[0], rtol=1e-12)
+
+
 def test_more_query_clusters_tighten_clustering_error():
     # "Effect of clustering": delta_q^2 falls as the number of query clusters grows, and the
     # attention-map error with it (Proposition 1 ties the two together).
