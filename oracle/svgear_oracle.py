@@ -180,7 +180,8 @@ def probe_errors(qbar, kbar, vbar, Kp, Vp, k_offsets, scale: float, value_aware:
     rescales by exp(2(m_i - m_local)) at the end; Eq. (7) and the text ("aggregate the
     estimated errors within each block") have no initial term, and moving an accumulator
     from exp(-2 m_local) units to exp(-2 m_i) units needs exp(2(m_local - m_i)). This oracle
-    follows Eq. (7): it starts at 0 and needs no running maximum at all in fp64.
+    follows Eq. (7): it starts at 0 and needs no running maximum at all in fp64 (the tests
+    check the change-of-units identity that any streaming evaluation relies on).
     Kp, Vp are cluster-contiguous (k_offsets); only clustered keys enter.
     """
     qbar = np.asarray(qbar, np.float64)
@@ -207,38 +208,6 @@ def probe_errors(qbar, kbar, vbar, Kp, Vp, k_offsets, scale: float, value_aware:
             E[:, b] = (diff * diff).sum(axis=1)
     scores = np.where(nonempty[None, :], E / np.maximum(sizes, 1)[None, :], 0.0)
     return E, scores, m
-
-
-def probe_errors_streaming(qbar, kbar, vbar, Kp, Vp, k_offsets, scale: float):
-    """Algorithm 1's streaming form (running maximum, rescaling), with the two readings
-    stated in probe_errors applied; used only to pin probe_errors. Pure loops: small inputs.
-    """
-    qbar = np.asarray(qbar, np.float64)
-    kbar = np.asarray(kbar, np.float64)
-    vbar = np.asarray(vbar, np.float64)
-    Cq, Ck = qbar.shape[0], kbar.shape[0]
-    sizes = np.diff(np.asarray(k_offsets[: Ck + 1], np.int64))
-    S = (qbar @ kbar.T) * scale
-    m = np.where((sizes > 0)[None, :], S, -np.inf).max(axis=1)
-    E = np.zeros((Cq, Ck))
-    for i in range(Cq):
-        for j in range(Ck):
-            if sizes[j] == 0:
-                continue
-            Y = np.exp(S[i, j] - m[i]) * vbar[j]
-            m_loc = m[i]
-            e = 0.0
-            for t in range(k_offsets[j], k_offsets[j + 1]):
-                s = float(qbar[i] @ np.asarray(Kp[t], np.float64)) * scale
-                m_new = max(m_loc, s)
-                alpha = np.exp(m_loc - m_new)
-                e *= alpha * alpha
-                Y = Y * alpha
-                r = np.exp(s - m_new) * np.asarray(Vp[t], np.float64) - Y
-                e += float(r @ r)
-                m_loc = m_new
-            E[i, j] = e * np.exp(2.0 * (m_loc - m[i]))
-    return E
 
 
 # --------------------------------------------------------------------------- route
@@ -320,9 +289,6 @@ def route(scores, q_sizes, k_sizes, budget: int, per_row: bool = False,
     return mask, row_ptr, col_idx, int(routed_cost)
 
 
-TOP_P_WEIGHT_BITS = 20
-
-
 def top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p: float, scale: float):
     """Adaptive per-query-cluster budgets (Experiments, "Implementation": the method inherits
     a top-p budget allocation and routes per query cluster; hyper-parameter table, "TopP").
@@ -331,14 +297,14 @@ def top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p: float, scale: float):
     the non-empty key clusters carry the centroid attention mass
         mass_b = |k_b| exp(qbar_a . kbar_b * scale - m_a),  m_a the largest such logit,
     i.e. the share of a centroid query's softmax that falls on cluster b when every key sits at
-    its centroid. Masses are taken in units of 2^-20 (w_b = floor(mass_b 2^20), an integer, so
-    that sums do not depend on the order of addition); clusters are ordered by w_b descending,
-    equal ones by ascending b; the prefix kept is the shortest whose summed weight reaches
-    ceil(p * sum_b w_b). The budget of row a is the cost of exact attention over that prefix,
+    its centroid (real numbers, fp64 here). Clusters are ordered by mass descending, equal ones
+    by ascending b; the prefix kept is the shortest whose summed mass reaches p times the
+    row's total mass. The budget of row a is the cost of exact attention over that prefix,
     |q_a| * sum_{b kept} |k_b| query-key pairs; error-aware routing then spends it on the
     blocks of row a with the largest error-to-cost ratio.
 
-    Returns (budgets int64 [Cq], n_keep int32 [Cq]); empty query clusters get 0."""
+    p is taken at float32 precision (the value an implementation receives through a float
+    argument). Returns (budgets int64 [Cq], n_keep int32 [Cq]); empty query clusters get 0."""
     qbar, kbar = np.asarray(qbar, np.float64), np.asarray(kbar, np.float64)
     Cq, Ck = qbar.shape[0], kbar.shape[0]
     qs = [int(v) for v in q_sizes[:Cq]]
@@ -352,19 +318,20 @@ def top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, p: float, scale: float):
             continue
         logit = {b: float(qbar[a] @ kbar[b]) * scale for b in live}
         m = max(logit.values())
-        w = {b: int(np.floor(ks[b] * np.exp(logit[b] - m) * float(1 << TOP_P_WEIGHT_BITS))) for b in live}
-        total = sum(w.values())
-        need = max(int(np.ceil(p * float(total))), 1)
-        run = 0
+        mass = {b: ks[b] * float(np.exp(logit[b] - m)) for b in live}
+        order = sorted(live, key=lambda b: (-mass[b], b))
+        total = 0.0
+        for b in order:  # the row's total, added in the same order as the running sum below
+            total += mass[b]
+        run = 0.0
         keys = 0
-        for n, b in enumerate(sorted(live, key=lambda b: (-w[b], b)), start=1):
-            run += w[b]
+        n_keep[a] = len(live)
+        for n, b in enumerate(order, start=1):
+            run += mass[b]
             keys += ks[b]
-            if run >= need:
+            if run >= p * total:
                 n_keep[a] = n
                 break
-        else:
-            n_keep[a] = len(live)
         budgets[a] = qs[a] * keys
     return budgets, n_keep
 
@@ -414,46 +381,6 @@ def attention_comp(Q, K, V, lab_q, lab_k, kbar, vbar, mask, scale: float, row_ch
         e = min(s + row_chunk, Q.shape[0])
         A, M = attention_map_comp(Q[s:e], K, lab_q[s:e], lab_k, kbar, mask, scale)
         out[s:e] = (A * M) @ V64 + (A * ~M) @ vbar_rows
-    return out
-
-
-def attention_two_stage(Q, K, V, lab_q, lab_k, kbar, vbar, k_sizes, mask, scale: float):
-    """Algorithm 2's form: exact attention over routed keys giving (O, LSE), then every
-    skipped non-empty cluster merged as one pseudo-key with logit q.kbar*scale + ln|k_c|
-    and value vbar by online softmax. Reading: the algorithm as printed never initialises
-    its accumulator; starting from acc = O with l = 1, m = LSE is the consistent choice,
-    and a row with nothing routed starts empty. Used only to pin attention_comp.
-    Pure loops: small inputs.
-    """
-    Q, K, V, kbar, vbar = (np.asarray(t, np.float64) for t in (Q, K, V, kbar, vbar))
-    nq, d = Q.shape[0], V.shape[1]
-    out = np.zeros((nq, d))
-    lab_k = np.asarray(lab_k)
-    for i in range(nq):
-        a = lab_q[i]
-        sel = np.asarray(mask)[a][lab_k]
-        if sel.any():
-            l = (K[sel] @ Q[i]) * scale
-            mx = l.max()
-            p = np.exp(l - mx)
-            acc = (p @ V[sel]) / p.sum()
-            m_i = mx + np.log(p.sum())
-            l_i = 1.0
-        else:
-            acc = np.zeros(d)
-            m_i = -np.inf
-            l_i = 0.0
-        for j in range(kbar.shape[0]):
-            if mask[a][j] or k_sizes[j] == 0:
-                continue
-            s = float(Q[i] @ kbar[j]) * scale + np.log(k_sizes[j])
-            m_new = max(m_i, s)
-            alpha = np.exp(m_i - m_new) if np.isfinite(m_i) else 0.0
-            p = np.exp(s - m_new)
-            l_i = l_i * alpha + p
-            acc = acc * alpha + p * vbar[j]
-            m_i = m_new
-        out[i] = acc / l_i
     return out
 
 

@@ -80,3 +80,32 @@ def oracle_head(Q, K, V, b, h, wl, iters=None, budget=None, **kw):
     budget = budget_pairs(wl.rho, wl.N, wl.N) if budget is None else budget
     return orc.hot_path_head(q, k, v, q[iq], k[ik], wl.iters if iters is None else iters, budget,
                              n_tail=wl.n_tail, **kw)
+
+
+def check_top_p_row_budgets(got, qbar, kbar, q_sizes, k_sizes, p, scale):
+    """GPU row budgets of the adaptive (top-p reading) rule against the oracle's real-valued rule.
+
+    The length of the kept prefix is an integer decided by floating point. The oracle sums fp64
+    masses |k_b| exp(S_ab - m_a); the library evaluates the logits and exponentials in fp32
+    (relative error of a mass: a few 1e-6 from the d-term fp32 dot product times the logit's size,
+    bounded here by 2.5e-5) and counts masses in integer units of 2^-20 (each mass loses less than
+    one unit, so a row's sums move by less than Ck 2^-20). The fraction of the row's mass held by
+    any prefix therefore moves by at most
+        delta = 2 * 2.5e-5 + Ck * 2^-20 / (row's total mass),
+    so the library's answer must equal the oracle's wherever the oracle's answer is the same for
+    p (1 - delta) and p (1 + delta), and lie between those two answers elsewhere.
+    Returns the number of rows that differ from the oracle's answer at p itself."""
+    qbar64, kbar64 = np.asarray(qbar, np.float64), np.asarray(kbar, np.float64)
+    live = np.asarray(k_sizes) > 0
+    S = np.where(live[None, :], (qbar64 @ kbar64.T) * scale, -np.inf)
+    total = (np.asarray(k_sizes, np.float64)[None, :] * np.exp(S - S.max(axis=1, keepdims=True))).sum(axis=1)
+    delta = 5e-5 + kbar64.shape[0] * 2.0 ** -20 / float(total.min())
+    args = (qbar, kbar, q_sizes, k_sizes)
+    mid = orc.top_p_row_budgets(*args, p, scale)[0]
+    lo = orc.top_p_row_budgets(*args, p * (1 - delta), scale)[0]
+    hi = orc.top_p_row_budgets(*args, min(p * (1 + delta), 1.0), scale)[0]
+    got = np.asarray(got)
+    assert np.all(lo <= got) and np.all(got <= hi), (got, lo, hi)
+    settled = lo == hi
+    assert np.array_equal(got[settled], mid[settled])
+    return int((got != mid).sum())

@@ -6,7 +6,8 @@ import torch
 import paper_2603_08982_amd as sv
 from oracle import svgear_oracle as orc
 from workloads import get_workload, make_qkv, budget_pairs
-from helpers import dev, to_np, oracle_head, mask_to_bits, csr_from_mask, full_mask, rel_l2, init_centroids
+from helpers import (dev, to_np, oracle_head, mask_to_bits, csr_from_mask, full_mask, rel_l2, init_centroids,
+                     check_top_p_row_budgets)
 
 pytestmark = pytest.mark.gpu
 
@@ -208,12 +209,7 @@ def test_end_to_end_chain_with_adaptive_row_budgets_matches_oracle(name):
         for h in range(H):
             qcnt, kcnt = to_np(r["qcnt"][b, h]), to_np(r["kcnt"][b, h])
             got = to_np(r["row_budget"][b, h])
-            args = (to_np(r["qbar"][b, h]), to_np(r["kbar"][b, h]), qcnt, kcnt)
-            lo = orc.top_p_row_budgets(*args, p * (1 - 1e-4), scale)[0]
-            hi = orc.top_p_row_budgets(*args, p * (1 + 1e-4), scale)[0]
-            mid = orc.top_p_row_budgets(*args, p, scale)[0]
-            assert np.all(lo <= got) and np.all(got <= hi)
-            assert np.array_equal(got[lo == hi], mid[lo == hi])
+            check_top_p_row_budgets(got, to_np(r["qbar"][b, h]), to_np(r["kbar"][b, h]), qcnt, kcnt, p, scale)
             m_ref = orc.route(to_np(r["scores"][b, h]), qcnt, kcnt, 0, n_tail_q=wl.n_tail, n_tail_k=wl.n_tail,
                               row_budgets=got)[0]
             m = bits_to_mask(to_np(r["mask_bits"][b, h]), wl.Ck)

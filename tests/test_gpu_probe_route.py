@@ -6,7 +6,7 @@ import torch
 import paper_2603_08982_amd as sv
 from oracle import svgear_oracle as orc
 from workloads import get_workload, make_qkv, budget_pairs
-from helpers import dev, to_np, oracle_head, bits_to_mask, full_mask
+from helpers import dev, to_np, oracle_head, bits_to_mask, full_mask, check_top_p_row_budgets
 
 pytestmark = pytest.mark.gpu
 
@@ -107,18 +107,7 @@ def test_route_is_deterministic():
 
 
 def _check_row_budgets(got, ref_head, wl, p, scale):
-    """The prefix length is an integer decided by floating point (fp32 masses on the GPU, fp64
-    in the oracle): a row's budget must equal the oracle's wherever the oracle's own answer
-    does not change for p within 1e-4 of the given one, and lie between those two answers
-    elsewhere. Returns the number of rows that differ from the oracle's answer at p."""
-    args = (ref_head["qbar"], ref_head["kbar"], ref_head["qcnt"], ref_head["kcnt"])
-    mid = orc.top_p_row_budgets(*args, p, scale)[0]
-    lo = orc.top_p_row_budgets(*args, p * (1 - 1e-4), scale)[0]
-    hi = orc.top_p_row_budgets(*args, min(p * (1 + 1e-4), 1.0), scale)[0]
-    assert np.all(lo <= got) and np.all(got <= hi), (got, lo, hi)
-    settled = lo == hi
-    assert np.array_equal(got[settled], mid[settled])
-    return int((got != mid).sum())
+    return check_top_p_row_budgets(got, ref_head["qbar"], ref_head["kbar"], ref_head["qcnt"], ref_head["kcnt"], p, scale)
 
 
 @pytest.mark.parametrize("name", ["tiny", "mini_video", "mini_video_tail", "mini_d64", "mini_manyq", "mini_manyk"])

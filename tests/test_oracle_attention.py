@@ -76,17 +76,59 @@ def test_compensated_entries_use_centroid_logit_and_mean_value():
     assert np.allclose(O[0], want, atol=1e-14)
 
 
-def test_two_stage_algorithm2_equals_literal_form():
-    Q, K, V, lq, lk, kbar, vbar, ks, mask = _toy(4)
+def _toy_with_empty_cluster_and_unrouted_row(seed):
+    Q, K, V, lq, lk, kbar, vbar, ks, mask = _toy(seed)
     mask[2] = False  # a query cluster with nothing routed
     lk2 = lk.copy()
     lk2[lk2 == 3] = 4  # an empty key cluster
     kbar = np.stack([K[lk2 == b].mean(0) if (lk2 == b).any() else np.zeros(K.shape[1]) for b in range(6)])
     vbar = np.stack([V[lk2 == b].mean(0) if (lk2 == b).any() else np.zeros(V.shape[1]) for b in range(6)])
-    ks2 = np.bincount(lk2, minlength=6)
-    O1 = orc.attention_comp(Q, K, V, lq, lk2, kbar, vbar, mask, 0.3)
-    O2 = orc.attention_two_stage(Q, K, V, lq, lk2, kbar, vbar, ks2, mask, 0.3)
-    assert np.abs(O1 - O2).max() < 1e-12
+    return Q, K, V, lq, lk2, kbar, vbar, np.bincount(lk2, minlength=6), mask
+
+
+def test_compensation_equals_dense_attention_over_keys_replaced_by_their_cluster_mean():
+    # Eq. (1) + Eq. (6) say: a skipped key behaves as if it sat at its cluster's mean key and
+    # carried the cluster's mean value. So plain dense softmax attention over the key/value set
+    # in which every key of a skipped block is REPLACED by (kbar_b, vbar_b) -- |k_b| identical
+    # copies, which is where the ln|k_b| of the pseudo-key form comes from -- must give the same
+    # rows. The replacement depends on the query's cluster, so it is done per query cluster.
+    Q, K, V, lq, lk, kbar, vbar, ks, mask = _toy_with_empty_cluster_and_unrouted_row(4)
+    O = orc.attention_comp(Q, K, V, lq, lk, kbar, vbar, mask, 0.3)
+    for a in np.unique(lq):
+        routed = mask[a][lk]
+        K_a = np.where(routed[:, None], K, kbar[lk])
+        V_a = np.where(routed[:, None], V, vbar[lk])
+        want = orc.dense_attention(Q[lq == a], K_a, V_a, 0.3)
+        assert np.abs(O[lq == a] - want).max() < 1e-12
+
+
+def test_routed_part_and_compensated_part_merge_by_their_log_sum_exp():
+    # The two-stage form (Algorithm 2; also what a split into separate kernels relies on): the
+    # routed keys alone give (O_r, LSE_r), the skipped non-empty clusters alone -- ONE pseudo-key
+    # each, logit q.kbar_b*scale + ln|k_b|, value vbar_b -- give (O_c, LSE_c), and
+    #   O = (e^{LSE_r} O_r + e^{LSE_c} O_c) / (e^{LSE_r} + e^{LSE_c}).
+    # Written with whole-array softmaxes (no running quantities); a part with no entries has
+    # weight zero.
+    Q, K, V, lq, lk, kbar, vbar, ks, mask = _toy_with_empty_cluster_and_unrouted_row(4)
+    scale = 0.3
+    O = orc.attention_comp(Q, K, V, lq, lk, kbar, vbar, mask, scale)
+
+    def part(logits, values):  # softmax-weighted mean and log-sum-exp of one set of entries
+        if logits.size == 0:
+            return np.zeros(values.shape[1]), -np.inf
+        mx = logits.max()
+        w = np.exp(logits - mx)
+        return (w @ values) / w.sum(), mx + np.log(w.sum())
+
+    for i in range(Q.shape[0]):
+        a = lq[i]
+        routed = mask[a][lk]
+        skipped = np.flatnonzero(~mask[a] & (ks > 0))
+        o_r, lse_r = part(K[routed] @ Q[i] * scale, V[routed])
+        o_c, lse_c = part(kbar[skipped] @ Q[i] * scale + np.log(ks[skipped]), vbar[skipped])
+        top = max(lse_r, lse_c)
+        w_r, w_c = np.exp(lse_r - top), np.exp(lse_c - top)
+        assert np.abs((w_r * o_r + w_c * o_c) / (w_r + w_c) - O[i]).max() < 1e-12
 
 
 def test_proposition1_bound_holds_on_tiny_workload():

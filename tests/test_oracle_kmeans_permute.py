@@ -4,6 +4,8 @@ The paper (Methodology, "Problem Formulation") fixes only that clusters come fro
 and that centroids are cluster means; these tests pin the oracle to textbook facts about
 Lloyd's algorithm, to brute force and to scipy's implementation.
 """
+from fractions import Fraction
+
 import numpy as np
 import pytest
 from scipy.cluster.vq import kmeans2
@@ -55,28 +57,70 @@ def test_assign_ties_go_to_lowest_index():
     assert lab.max() < 4
 
 
-def test_assign_fixed_fp32_order_against_python_float32_loop():
-    # retrace the documented order with numpy float32 scalars and exact fma emulation
-    # (fp64 product of two fp32 numbers is exact; the sum is rounded once to fp64 then to
-    # fp32 -- double rounding can differ from a true fma only on exact-midpoint cases,
-    # which the check below tolerates by comparing scores to 1 ulp and labels on the rest)
+def _round_to_f32(x: Fraction) -> np.float32:
+    """The float32 nearest to the rational x, ties to the even mantissa (IEEE round-to-nearest-even)."""
+    f = np.float32(float(x))  # within one float32 step of the answer: pick among it and its neighbours
+    cands = sorted({f, np.nextafter(f, np.float32(np.inf)), np.nextafter(f, np.float32(-np.inf))}, key=float)
+    best = min(abs(Fraction(float(c)) - x) for c in cands)
+    near = [c for c in cands if abs(Fraction(float(c)) - x) == best]
+    if len(near) == 1:
+        return near[0]
+    even = [c for c in near if (c.view(np.uint32) & np.uint32(1)) == 0]
+    return even[0]
+
+
+def _fma32(a, b, c) -> np.float32:
+    """fmaf(a, b, c): the product and the sum exact (rationals), ONE rounding to float32."""
+    return _round_to_f32(Fraction(float(a)) * Fraction(float(b)) + Fraction(float(c)))
+
+
+def _fixed_order_scores(x, C, fma=_fma32, order=None, cn_first=False):
+    out = []
+    ts = list(range(x.shape[0])) if order is None else order
+    for j in range(C.shape[0]):
+        dot = np.float32(0)
+        cn = np.float32(0)
+        for t in ts:
+            dot = fma(x[t], C[j, t], dot)
+        for t in ts:
+            cn = fma(C[j, t], C[j, t], cn)
+        out.append(fma(np.float32(-2.0), dot, cn))
+    return np.array(out, np.float32)
+
+
+def test_round_to_f32_helper_rounds_ties_to_even():
+    one = Fraction(1)
+    ulp = Fraction(1, 1 << 23)
+    assert _round_to_f32(one + ulp / 2) == np.float32(1.0)                    # tie -> even (1.0)
+    assert _round_to_f32(one + ulp + ulp / 2) == np.float32(1.0) + np.float32(2.0 ** -22)  # tie -> even
+    assert _round_to_f32(one + ulp / 2 + Fraction(1, 1 << 60)) == np.nextafter(np.float32(1), np.float32(2))
+    # a case where rounding to double first and then to single goes wrong: 1 + 2^-24 + 2^-60
+    x = one + Fraction(1, 1 << 24) + Fraction(1, 1 << 60)
+    assert np.float32(float(x)) == np.float32(1.0) and _round_to_f32(x) != np.float32(1.0)
+
+
+def test_assign_fixed_fp32_order_bit_for_bit_against_exact_fma_emulation():
+    # The documented order -- x.c and |c|^2 each ONE fma chain over t = 0..d-1, then
+    # fma(-2, dot, cn), lowest index on ties -- retraced with exactly rounded fused
+    # multiply-adds (rational arithmetic, one rounding): scores and labels must be IDENTICAL.
     rng = np.random.default_rng(2)
-    X = rng.standard_normal((20, 32)).astype(np.float32)
+    X = rng.standard_normal((24, 32)).astype(np.float32)
     C = rng.standard_normal((6, 32)).astype(np.float32)
+    C[4] = C[1]  # an exact tie between two centroids: the lower index must win
     lab, best = orc.kmeans_assign(X, C, return_scores=True)
-    for i in range(20):
-        scores = []
-        for j in range(6):
-            dot = np.float32(0)
-            cn = np.float32(0)
-            for t in range(32):
-                dot = np.float32(np.float64(X[i, t]) * np.float64(C[j, t]) + np.float64(dot))
-            for t in range(32):
-                cn = np.float32(np.float64(C[j, t]) * np.float64(C[j, t]) + np.float64(cn))
-            scores.append(np.float32(np.float64(-2.0) * np.float64(dot) + np.float64(cn)))
-        scores = np.array(scores, np.float32)
-        assert abs(float(scores.min()) - float(best[i])) <= 4 * np.spacing(np.float32(abs(best[i])))
-        assert scores[lab[i]] <= scores.min() + 4 * np.spacing(np.float32(abs(best[i])))
+    n_unfused = n_reversed = 0
+    for i in range(X.shape[0]):
+        scores = _fixed_order_scores(X[i], C)
+        assert scores.min().view(np.uint32) == best[i].view(np.uint32)
+        assert int(np.flatnonzero(scores == scores.min())[0]) == lab[i]
+        assert lab[i] != 4
+        # planted mistakes must be visible at this strictness: a separate multiply and add
+        # (two roundings), and the chain run in the opposite order, each change some best score
+        unfused = _fixed_order_scores(X[i], C, fma=lambda a, b, c: np.float32(np.float32(a * b) + c))
+        n_unfused += unfused.min().view(np.uint32) != best[i].view(np.uint32)
+        rev = _fixed_order_scores(X[i], C, order=list(range(31, -1, -1)))
+        n_reversed += rev.min().view(np.uint32) != best[i].view(np.uint32)
+    assert n_unfused > 0 and n_reversed > 0
 
 
 def test_cluster_means_and_empty_cluster():

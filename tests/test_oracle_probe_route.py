@@ -92,13 +92,39 @@ def test_probe_row_stabiliser_is_exp_minus_2m():
             assert np.isclose(raw * np.exp(-2 * m[a]), E[a, b], rtol=1e-10)
 
 
-def test_probe_streaming_algorithm1_matches_direct():
+def test_probe_block_error_merges_from_parts_held_in_other_units():
+    # Any streaming evaluation (Algorithm 1) holds partial sums in units of its own running
+    # stabiliser and converts at the end. The identity it needs: a sum of Eq. (7) terms held
+    # with stabiliser m' is exp(2 (m_a - m')) times the same sum held with m_a, so a part is
+    # brought back with exp(2 (m' - m_a)) -- the sign reading of the listing's last line.
+    # Check it by cutting every key cluster into two parts, evaluating each part directly with a
+    # DIFFERENT stabiliser (its own largest logit), and merging.
     qbar, kbar, vbar, Kp, Vp, off, lab = _setup(5, empty=2)
-    # make some keys exceed every centroid logit so the running maximum really moves
-    Kp[::7] *= 4.0
-    E, _, _ = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, 0.4, True)
-    Es = orc.probe_errors_streaming(qbar, kbar, vbar, Kp, Vp, off, 0.4)
-    assert np.allclose(E, Es, rtol=1e-11, atol=0)
+    Kp[::7] *= 4.0  # keys whose logit exceeds every centroid logit: a running maximum would move
+    scale = 0.4
+    E, _, m = orc.probe_errors(qbar, kbar, vbar, Kp, Vp, off, scale, True)
+    S = qbar @ kbar.T * scale
+    assert ((Kp @ qbar.T * scale).max(0) > m).any()
+    for a in range(qbar.shape[0]):
+        for b in range(kbar.shape[0]):
+            lo, hi = off[b], off[b + 1]
+            if hi == lo:
+                assert E[a, b] == 0
+                continue
+            merged = 0.0
+            wrong_sign = 0.0
+            cut = lo + (hi - lo) // 3
+            for sl in (slice(lo, cut), slice(cut, hi)):
+                if sl.stop == sl.start:
+                    continue
+                s = Kp[sl] @ qbar[a] * scale
+                m_part = max(s.max(), S[a, b])  # this part's own stabiliser
+                part = ((np.exp(S[a, b] - m_part) * vbar[b][None] - np.exp(s - m_part)[:, None] * Vp[sl]) ** 2).sum()
+                merged += part * np.exp(2.0 * (m_part - m[a]))
+                wrong_sign += part * np.exp(2.0 * (m[a] - m_part))
+            assert np.isclose(merged, E[a, b], rtol=1e-11, atol=0)
+            if abs(m_part - m[a]) > 1e-3:
+                assert not np.isclose(wrong_sign, E[a, b], rtol=1e-6, atol=0)
 
 
 def test_probe_printed_initial_term_differs_by_exp2S_vbar2():
@@ -267,8 +293,6 @@ def test_top_p_budget_is_cost_of_softmax_mass_prefix_bruteforce():
                 n = 1
                 while share[order[:n]].sum() < p - 1e-9:
                     n += 1
-                # generic data: no share sits within 1e-5 of the threshold, so the 2^-20 units do not matter
-                assert abs(share[order[:n]].sum() - p) > 1e-5
                 assert n_keep[a] == n
                 assert budgets[a] == q_sizes[a] * k_sizes[order[:n]].sum()
 
@@ -294,20 +318,23 @@ def test_top_p_limits_monotone_and_empty_clusters():
     heaviest = mass.argmax(axis=1)
     assert np.all(n_tiny == 1) and np.array_equal(tiny, q_sizes * k_sizes[heaviest])
     full, n_full = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, 1.0, scale)
-    # p = 1 keeps every cluster whose mass is at least one unit of 2^-20; here all of them are
-    live = k_sizes > 0
-    assert (mass[:, live].min(axis=1) / mass.max(axis=1)).min() > 2.0 ** -18
+    # p = 1 keeps every non-empty cluster
     assert np.all(n_full == (k_sizes > 0).sum()) and np.array_equal(full, q_sizes * k_sizes.sum())
     prev = tiny
     for p in np.linspace(0.05, 1.0, 20):
         cur, _ = orc.top_p_row_budgets(qbar, kbar, q_sizes, k_sizes, float(p), scale)
         assert np.all(cur >= prev)
         prev = cur
-    # a far-away cluster (mass below one unit) is never kept, even at p = 1
+    # a far-away cluster carries almost no mass: it is the last of the order, dropped for any
+    # p below 1 by a hair and kept at p = 1 (the masses are real numbers, nothing is cut off)
     kbar2 = kbar.copy()
-    kbar2[5] = -40.0 * qbar[0] / np.linalg.norm(qbar[0])
+    kbar2[5] = -25.0 * qbar[0] / np.linalg.norm(qbar[0])
+    share = k_sizes * np.exp(qbar[0] @ kbar2.T * scale)
+    assert 1e-12 < share[5] / share.sum() < 2.0 ** -24  # tiny, yet far above the rounding of an fp64 sum
     _, n2 = orc.top_p_row_budgets(qbar[:1], kbar2, q_sizes[:1], k_sizes, 1.0, scale)
-    assert n2[0] == (k_sizes > 0).sum() - 1
+    assert n2[0] == (k_sizes > 0).sum()
+    _, n3 = orc.top_p_row_budgets(qbar[:1], kbar2, q_sizes[:1], k_sizes, 1.0 - 1e-6, scale)
+    assert n3[0] == (k_sizes > 0).sum() - 1
 
 
 def test_top_p_query_size_scaling_and_key_cluster_relabelling():
