@@ -42,7 +42,9 @@
 extern "C" {
 #endif
 
-typedef enum { SVGEAR_F32 = 0, SVGEAR_BF16 = 1 } svgear_dtype;
+/* The last enumerator only widens the enum's value range to that of int, so that a caller's
+ * out-of-range value reaches the argument checks as a defined value (and is rejected there). */
+typedef enum { SVGEAR_F32 = 0, SVGEAR_BF16 = 1, SVGEAR_DTYPE_INT_RANGE = 0x7fffffff } svgear_dtype;
 
 typedef enum {
   SVGEAR_OK = 0,
@@ -146,6 +148,11 @@ int svgear_permute_rows(const int32_t* perm, int B, int H, int64_t N, int n_tens
  *   Sbar_ab = qbar_a.kbar_b*scale,  m_a = max over non-empty b of Sbar_ab
  * (PLAIN: the same with the value vectors dropped), and scores[a,b] = E[a,b]/|k_b| -- the
  * block's error-to-cost ratio, |q_a| cancelling. Empty key clusters score 0.
+ * The exponents Sbar_ab - m_a (<= 0 by construction) and qbar_a.k_j*scale - m_a are capped at 40
+ * before the exponential so that the squares stay inside fp32: a key whose logit exceeds EVERY
+ * centroid logit of its row by more than 40 (e^40 ~ 2e17 times the weight of the row's best
+ * centroid) is scored as if the excess were 40, i.e. such a score is a lower bound of Eq. (7), not
+ * its value. Up to that excess the scores follow Eq. (7) / Eq. (5) to fp32 accuracy.
  * Route: blocks with both sizes non-zero are ordered by score descending (NaN as +inf),
  * ties by ascending a*Ck+b; cost of a block is |q_a||k_b|; walking that order, blocks are
  * routed while the summed cost stays <= the budget, stopping at the first that does not fit.
@@ -211,9 +218,10 @@ int svgear_probe_route_top_p(const float* qbar, const float* kbar, const float* 
  *   q_offsets, k_offsets, mask_bits, row_ptr, col_idx as produced by svgear_probe_route
  *   op  [BH,Nq,d] dt out (permuted order);  lse [BH,Nq] fp32 out or NULL: natural log of the
  *   softmax denominator of each row.
- * Limit of the bf16 kernels: the per-key-cluster tables sit in LDS beside the K/V tile buffers
- * (12 bytes per key cluster), which allows Ck up to about 2500 for d = 128 and 8192 for d = 64;
- * SVGEAR_ERR_UNSUPPORTED beyond that. fp32 has no such limit.
+ * Limits of the bf16 kernels (SVGEAR_ERR_UNSUPPORTED beyond them; fp32 has neither): the
+ * per-key-cluster tables sit in LDS beside the K/V tile buffers (12 bytes per key cluster), which
+ * allows Ck up to about 2500 for d = 128 and 8192 for d = 64; for d = 128 the K/V rows of a head are
+ * addressed by 32-bit byte offsets, so Nk <= 16,777,215 keys per head.
  */
 size_t svgear_sparse_attn_comp_workspace(int B, int H, int64_t Nq, int64_t Nk, int d, int Cq,
                                          int Ck);

@@ -17,28 +17,37 @@ FLAGS = [
 ]
 
 
-def _compile(src: str, objdir: str) -> str:
+# host code only (argument checks, launch logic) under AddressSanitizer / UBSan; device code is unchanged
+HOST_SANITIZE_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                       "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def _compile(src: str, objdir: str, extra=()) -> str:
     obj = os.path.join(objdir, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
     return obj
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles every source and links the shared library; always rebuilds."""
-    objdir = os.path.join(_HERE, "_build")
+def build(verbose: bool = False, lib: str = LIB, objdir: str | None = None, host_sanitize: bool = False) -> str:
+    """Compiles every source and links the shared library; always rebuilds. host_sanitize=True
+    builds a copy whose HOST code runs under AddressSanitizer and UBSan (for a CPU test binary;
+    give it its own `lib` and `objdir`)."""
+    objdir = os.path.join(_HERE, "_build") if objdir is None else objdir
     os.makedirs(objdir, exist_ok=True)
+    extra = HOST_SANITIZE_FLAGS if host_sanitize else ()
     with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, objdir), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+        objs = list(ex.map(lambda s: _compile(s, objdir, extra), SOURCES))
+    link_extra = ["-fsanitize=address", "-fsanitize=undefined"] if host_sanitize else []
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, *objs, "-o", lib]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":

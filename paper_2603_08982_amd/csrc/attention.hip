@@ -247,6 +247,8 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
   if ((int64_t)BH * ((int64_t)ceil_div(Nq, 64) + Cq + 1) > INT32_MAX / 2) return SVGEAR_ERR_UNSUPPORTED;
   if (part != 0 && !(dt == SVGEAR_BF16 && d == 128)) return SVGEAR_ERR_UNSUPPORTED;
   if (dt == SVGEAR_BF16 && attn_bf16_lds_bytes(d, Ck) > 160 * 1024) return SVGEAR_ERR_UNSUPPORTED;
+  // the d = 128 bf16 kernel addresses K/V rows of a head by 32-bit byte offsets (256 bytes a row)
+  if (dt == SVGEAR_BF16 && d == 128 && Nk > (int64_t)(UINT32_MAX / 256)) return SVGEAR_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   Workspace w(ws, ws_bytes);
   const int BM = attn_bm(dt, d);

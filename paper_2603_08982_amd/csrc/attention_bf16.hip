@@ -394,25 +394,6 @@ __device__ __forceinline__ bf16x8 tr_pair(const unsigned char* lds_base, int off
   return c.v;
 }
 
-// 16 bytes per lane from global memory straight into LDS: the wave's 64 lanes fill 1 KB
-// starting at LDS byte address `lds_addr` (wave-uniform), lane l at lds_addr + 16 l.
-// Written as inline assembly so that the compiler does not treat every later LDS read as
-// dependent on the copy (it would drain the copies before the first read of each tile);
-// completion is tracked by hand with vmcnt.
-__device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
-}
-// Same copy with the global address given as a wave-uniform base plus a 32-bit byte offset
-// per lane (no 64-bit vector arithmetic).
-__device__ __forceinline__ void async_copy_16B(const void* gbase, uint32_t byte_off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
-               :
-               : "v"(byte_off), "s"(gbase), "s"(lds_addr)
-               : "memory", "m0");
-}
 // A wave-uniform pointer the compiler could not prove uniform, moved to scalar registers.
 __device__ __forceinline__ const void* uniform_ptr(const void* p) {
   const uint64_t v = reinterpret_cast<uint64_t>(p);
@@ -431,8 +412,6 @@ static inline size_t lds_bytes_d128(int Ck, int stages) {
   return kv + (size_t)(stages + 2) * BN * 4 + lw + align_up(seg, 16);
 }
 
-// vmcnt(n) with expcnt and lgkmcnt left unconstrained (gfx9 s_waitcnt encoding)
-#define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 // NW waves of 32 query rows (three per SIMD); NSTAGE K/V tile buffers. The first CW waves of
 // the workgroup (the oldest wave of every SIMD, which finishes its step first) issue the tile

@@ -86,6 +86,35 @@ __device__ __forceinline__ int64_t head_base(const Strides& s, int bh, int H) {
   return (int64_t)(bh / H) * s.b + (int64_t)(bh % H) * s.h;
 }
 
+// ---- asynchronous global -> LDS copies -------------------------------------------------
+// 16 (4) bytes per lane from global memory straight into LDS: the wave's 64 lanes fill 1 KB
+// (256 B) starting at the wave-uniform LDS byte address `lds_addr`, lane l at lds_addr + 16 l
+// (4 l). Written as inline assembly so that the compiler does not treat every later LDS read
+// as dependent on the copy (it would drain the copies before the first read of each tile);
+// completion is tracked by hand with SVGEAR_WAIT_VMCNT.
+__device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+// Same copy with the global address given as a wave-uniform base plus a 32-bit byte offset
+// per lane (no 64-bit vector arithmetic).
+__device__ __forceinline__ void async_copy_16B(const void* gbase, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+               :
+               : "v"(byte_off), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy_4B(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+// vmcnt(n) with expcnt and lgkmcnt left unconstrained (gfx9 s_waitcnt encoding)
+#define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
 // ---- internal cross-file entry points ------------------------------------------------
 // Stable counting sort of token indices by label (tail tokens = pseudo-cluster C).
 // chunk_hist: scratch of BH * sort_chunks(N) * (C+1) int32.

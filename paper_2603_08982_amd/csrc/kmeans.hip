@@ -114,16 +114,6 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
   }
 }
 
-// 16 bytes per lane from global memory straight into LDS (lane l lands at lds_addr + 16 l).
-// Inline assembly keeps the compiler from serialising later LDS reads behind the copy;
-// completion is tracked by hand with vmcnt.
-__device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
-}
-#define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 // x[row][2s + h] for s = 0..D/2-1 into xb[] (the B operand of k-step s for lane (row, h))
 template <int D>

@@ -263,22 +263,6 @@ value_stats_kernel(const float* __restrict__ vbar, const bf16_t* __restrict__ vp
   }
 }
 
-// 16 (4) bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16 l
-// (4 l). Inline assembly keeps the compiler from serialising later LDS reads behind the copy;
-// completion is tracked by hand with vmcnt.
-__device__ __forceinline__ void async_copy_16B(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
-}
-__device__ __forceinline__ void async_copy_4B(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
-}
-#define SVGEAR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 // Block errors with the logits qbar_a . k_j on bf16 MFMAs (qbar in three exact bf16 pieces,
 // so the logits carry fp32-level accuracy). One workgroup per (head, kProbeClusters consecutive
@@ -312,6 +296,9 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
   static_assert(32 % (RPI * 4) == 0 && (CPR == 16 || CPR == 8), "tile split / swizzle assume d = 64 or 128");
   __shared__ __attribute__((aligned(1024))) unsigned char ktile[kProbeStages][TILE_B];
   __shared__ __attribute__((aligned(256))) float stat[kProbeStages][64];  // [|delta|^2 x 32, vbar.delta x 32]
+  // scores of the workgroup's key clusters, per wave [query centroid][key cluster]: a row leaves
+  // as ONE 16-byte store at the end instead of kProbeClusters 4-byte stores a score row apart
+  __shared__ __attribute__((aligned(16))) float sc[4][32][kProbeClusters];
   const int bh = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -321,9 +308,20 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
   const bool live = wave_on && a < Cq;
   const int32_t* off = k_offsets + (int64_t)bh * (Ck + 2);
   const int b_lo = blockIdx.x * kProbeClusters, b_end = min(b_lo + kProbeClusters, Ck);
-  // empty key clusters score 0
-  for (int b = b_lo; b < b_end; ++b)
-    if (off[b + 1] <= off[b] && live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + b] = 0.f;
+  // empty key clusters score 0 (each wave reads and writes its own part of sc only)
+  if (lh == 0) {
+#pragma unroll
+    for (int i = 0; i < kProbeClusters; ++i) sc[wave][li][i] = 0.f;
+  }
+  auto flush = [&]() {  // the wave's scores to global memory
+    if (!live || lh != 0) return;
+    float* dst = scores + ((int64_t)bh * Cq + a) * Ck + b_lo;
+    if (b_end - b_lo == kProbeClusters && (Ck % 4) == 0) {
+      *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(&sc[wave][li][0]);
+    } else {
+      for (int i = 0; i < b_end - b_lo; ++i) dst[i] = sc[wave][li][i];
+    }
+  };
   bf16x8 bq[3][KSN];
   if (wave_on) {
     const bf16_t* src = q3 + (((int64_t)bh * nab + ab) * 3 * KSN) * 512 + lane * 8;
@@ -382,7 +380,10 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
 
   Cursor fc{b_lo, 0, 0, 0};  // next block to copy
   seek(fc);
-  if (fc.b >= b_end) return;  // nothing but empty clusters (uniform over the workgroup)
+  if (fc.b >= b_end) {  // nothing but empty clusters (uniform over the workgroup)
+    flush();
+    return;
+  }
   Cursor cc = fc;             // block being computed
   int issued = 0;
   for (; issued < PF && fc.b < b_end; ++issued) {
@@ -461,11 +462,12 @@ block_error_mfma_kernel(const bf16_t* __restrict__ q3, const float* __restrict__
       else rank(std::true_type{});
       if (cc.j0 + 32 >= cc.end) {  // last block of the cluster
         const float Et = E + __shfl_xor(E, 32);
-        if (live && lh == 0) scores[((int64_t)bh * Cq + a) * Ck + cc.b] = Et / (float)(cc.end - cc.start);
+        if (lh == 0) sc[wave][li][cc.b - b_lo] = Et / (float)(cc.end - cc.start);
       }
     }
     advance(cc);
   }
+  flush();
 }
 
 }  // namespace

@@ -3,7 +3,7 @@ import numpy as np
 import torch
 
 from oracle import svgear_oracle as orc
-from workloads import kmeans_init_indices
+from workloads import kmeans_init_indices, structural_rows
 
 
 def dev():
@@ -109,3 +109,29 @@ def check_top_p_row_budgets(got, qbar, kbar, q_sizes, k_sizes, p, scale):
     settled = lo == hi
     assert np.array_equal(got[settled], mid[settled])
     return int((got != mid).sum())
+
+
+def check_sampled_rows(wl, Qh, Oh, Kp, Vp, qoff, koff, perm_q, kbar, vbar, mask_bits, row_ptr, rng, n_random=40,
+                       tol_pooled=1e-2, tol_row=2e-2, what=""):
+    """Output rows of one head (token order, Oh [N,d] on the device) against Eq. (1) + Eq. (6)
+    evaluated by the oracle on the GPU's own clustering and mask, on structurally chosen rows
+    (cluster and tile edges, smallest / largest cluster, rows with nothing / the most routed, text
+    rows) plus random ones. Every row must be within tol_row, all rows pooled within tol_pooled;
+    a failure names the row."""
+    named = structural_rows(qoff, row_ptr, wl.Cq, rng, n_random)
+    names = list(named)
+    rows = np.array([named[k] for k in names], np.int64)
+    mask = bits_to_mask(mask_bits, wl.Ck)
+    lq = np.repeat(np.arange(wl.Cq + 1), np.diff(qoff))
+    lk = np.repeat(np.arange(wl.Ck + 1), np.diff(koff))
+    kb = np.concatenate([kbar, np.zeros((1, wl.d), np.float32)])
+    vb = np.concatenate([vbar, np.zeros((1, wl.d), np.float32)])
+    tok = torch.from_numpy(perm_q[rows]).long().to(Qh.device)
+    ref = orc.attention_comp(to_np(Qh[tok]), Kp, Vp, lq[rows], lk, kb, vb, mask, orc.scale_of(wl.d), row_chunk=16)
+    got = to_np(Oh[tok])  # permuted row p of the output sits at token perm_q[p]
+    per_row = np.linalg.norm(got - ref, axis=1) / np.maximum(np.linalg.norm(ref, axis=1), 1e-30)
+    worst = int(np.argmax(per_row))
+    assert per_row[worst] <= tol_row, f"{what}: {names[worst]} (permuted row {rows[worst]}): rel-L2 {per_row[worst]:.3e}"
+    pooled = rel_l2(got, ref)
+    assert pooled <= tol_pooled, f"{what}: pooled rel-L2 {pooled:.3e} over {len(rows)} rows"
+    return pooled, float(per_row[worst])

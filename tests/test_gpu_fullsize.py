@@ -9,7 +9,8 @@ import torch
 import paper_2603_08982_amd as sv
 from oracle import svgear_oracle as orc
 from workloads import get_workload, make_qkv, budget_pairs, kmeans_init_indices
-from helpers import dev, to_np, init_centroids, bits_to_mask, full_mask, rel_l2, check_top_p_row_budgets
+from helpers import (dev, to_np, init_centroids, bits_to_mask, full_mask, rel_l2, check_top_p_row_budgets,
+                     check_sampled_rows)
 
 pytestmark = pytest.mark.gpu
 
@@ -38,7 +39,7 @@ def _printed_top_p():
 
 
 @pytest.mark.parametrize("name,top_p", [("wan", None), ("hunyuan", None), ("wan_c300", None),
-                                        ("wan_c300", _printed_top_p())])
+                                        ("wan_c300", _printed_top_p()), ("hunyuan_c400", None), ("wan_turbo", None)])
 def test_full_size_layer_sampled_parity(name, top_p):
     """top_p = None: one budget per head; 0.85 with 300/1000 clusters: the adaptive
     per-query-cluster budgets at the cluster counts and TopP of the paper's Wan2.2 row
@@ -51,6 +52,7 @@ def test_full_size_layer_sampled_parity(name, top_p):
     if top_p is None:
         assert int(r["routed_cost"].max()) <= budget
     for h in sorted({0, wl.H - 1}):
+        print(f"{name} top_p={top_p} head {h}", flush=True)
         qoff, koff = to_np(r["qoff"][0, h]), to_np(r["koff"][0, h])
         lab_q, lab_k = to_np(r["lab_q"][0, h]), to_np(r["lab_k"][0, h])
         # --- permutation: bit-exact given the labels (integer work)
@@ -101,20 +103,85 @@ def test_full_size_layer_sampled_parity(name, top_p):
         rp, ci = to_np(r["row_ptr"][0, h]), to_np(r["col_idx"][0, h])
         assert np.array_equal(rp[: m_ref.shape[0] + 1], rp_ref)
         assert np.array_equal(ci[: rp_ref[-1]], ci_ref)
-        # --- attention + compensation: sampled query rows against Eq. (1) + Eq. (6)
-        rows = np.sort(rng.choice(wl.N, 64, replace=False))
-        if wl.n_tail:
-            rows[-4:] = np.arange(wl.N - 4, wl.N)  # text rows: always exact against every key
-        lq = np.repeat(np.arange(wl.Cq + 1), np.diff(qoff))
-        lk = np.repeat(np.arange(wl.Ck + 1), np.diff(koff))
-        kb = np.concatenate([kbar, np.zeros((1, wl.d), np.float32)])
-        vb = np.concatenate([vbar, np.zeros((1, wl.d), np.float32)])
-        Qs = to_np(Q[0, h][torch.from_numpy(pq[rows]).long().to(dev())])
-        ref = orc.attention_comp(Qs, Kp, Vp, lq[rows], lk, kb, vb, mask, scale, row_chunk=16)
-        # the kernel writes row p of the permuted order to token perm_q[p] (un-permutation folded
-        # into its epilogue): permuted row p is O[perm_q[p]]
-        got_rows = to_np(O[0, h][torch.from_numpy(pq[rows]).long().to(dev())])
-        assert rel_l2(got_rows, ref) <= 1e-2
+        # --- attention + compensation: structural + random query rows against Eq. (1) + Eq. (6)
+        check_sampled_rows(wl, Q[0, h], O[0, h], Kp, Vp, qoff, koff, pq, kbar, vbar, to_np(r["mask_bits"][0, h]), rp,
+                           rng, what=f"{name} head {h}")
+
+
+def test_full_size_budget_extremes_wan():
+    """The budget sweep's end points at the Wan2.2 shape, 5 % and 50 % of the block cost, on ONE
+    clustering: a different mix of routed and compensated tiles per query row than at 25 %.
+    Routing must be the exact function of the library's own scores, sampled rows within tolerance."""
+    wl = get_workload("wan")
+    Q, K, V = make_qkv(wl, dev())
+    cq = init_centroids(Q, wl.Cq, wl.seed, 0)
+    ck = init_centroids(K, wl.Ck, wl.seed, 1)
+    scale = orc.scale_of(wl.d)
+    lab_q, qcnt, _ = sv.kmeans(Q, cq, 2)
+    lab_k, kcnt, vbar = sv.kmeans(K, ck, 2, x2=V)
+    perm_q, qoff, _ = sv.permute(lab_q, wl.Cq, [])
+    perm_k, koff, (Kp, Vp) = sv.permute(lab_k, wl.Ck, [K, V])
+    rng = np.random.default_rng(2)
+    for rho in (0.05, 0.50):
+        budget = budget_pairs(rho, wl.N, wl.N)
+        pr = sv.probe_route(cq, ck, vbar, Kp, Vp, qoff, koff, budget, scale)
+        O, _ = sv.sparse_attn_comp(Q, Kp, Vp, ck, vbar, qoff, koff, pr["mask_bits"], pr["row_ptr"], pr["col_idx"], scale,
+                                   q_perm=perm_q)
+        torch.cuda.synchronize()
+        assert int(pr["routed_cost"].max()) <= budget
+        dens = float(pr["routed_cost"].double().mean()) / float(wl.N) ** 2
+        assert rho - 0.01 <= dens <= rho
+        for h in (3, wl.H - 2):
+            print(f"wan rho={rho} head {h}", flush=True)
+            m_ref, rp_ref, ci_ref, cost_ref = orc.route(to_np(pr["scores"][0, h]), to_np(qcnt[0, h]), to_np(kcnt[0, h]),
+                                                        budget)
+            assert np.array_equal(bits_to_mask(to_np(pr["mask_bits"][0, h]), wl.Ck), full_mask(m_ref, wl.Cq, wl.Ck))
+            assert int(pr["routed_cost"][0, h]) == cost_ref
+            check_sampled_rows(wl, Q[0, h], O[0, h], to_np(Kp[0, h]), to_np(Vp[0, h]), to_np(qoff[0, h]),
+                               to_np(koff[0, h]), to_np(perm_q[0, h]), to_np(ck[0, h]), to_np(vbar[0, h]),
+                               to_np(pr["mask_bits"][0, h]), to_np(pr["row_ptr"][0, h]), rng, n_random=24,
+                               what=f"wan rho={rho} head {h}")
+
+
+def test_full_size_warm_started_second_step_wan():
+    """Denoising trajectory at the Wan2.2 shape: step 2 = step 1 + N(0, 0.05^2) drift (re-rounded to
+    bf16), k-means warm-started from step 1's centroids with 2 iterations, budget 20 %. The final
+    labels of step 2 are checked bit for bit against the oracle's assignment to the centroids after
+    its first iteration (the library is deterministic, so a 1-iteration run from the same carried
+    centroids reproduces them), the first iteration's labels against the carried centroids, and
+    sampled output rows of the step-2 layer against Eq. (1) + Eq. (6)."""
+    wl = get_workload("wan")
+    Q, K, V = make_qkv(wl, dev())
+    cq = init_centroids(Q, wl.Cq, wl.seed, 0)
+    ck = init_centroids(K, wl.Ck, wl.seed, 1)
+    budget = budget_pairs(0.20, wl.N, wl.N)
+    sv.attention_layer(Q, K, V, cq, ck, 2, budget)  # step 1: cold start, 2 iterations; cq, ck carried
+    gen = torch.Generator(device=dev())
+    gen.manual_seed(4242)
+    for X in (Q, K, V):
+        for h in range(wl.H):
+            X[0, h] = (X[0, h].float() + 0.05 * torch.randn(X[0, h].shape, generator=gen, device=dev())).to(X.dtype)
+    carried_q, carried_k = cq.clone(), ck.clone()
+    after1_q, after1_k = cq.clone(), ck.clone()
+    lab1_q, _, _ = sv.kmeans(Q, after1_q, 1)
+    lab1_k, _, _ = sv.kmeans(K, after1_k, 1, x2=V)
+    O, r = sv.attention_layer(Q, K, V, cq, ck, 2, budget)  # step 2
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    for h in (1, wl.H - 1):
+        print(f"wan warm-started step 2, head {h}", flush=True)
+        for X, carried, after1, lab1, lab2 in ((Q, carried_q, after1_q, lab1_q, r["lab_q"]),
+                                               (K, carried_k, after1_k, lab1_k, r["lab_k"])):
+            x = to_np(X[0, h])
+            assert np.array_equal(to_np(lab1[0, h]), orc.kmeans_assign(x, to_np(carried[0, h])))
+            assert np.array_equal(to_np(lab2[0, h]), orc.kmeans_assign(x, to_np(after1[0, h])))
+        moved = float((to_np(r["lab_k"][0, h]) != to_np(lab1_k[0, h])).mean())
+        assert moved < 0.5  # a warm start: most keys keep their cluster between the two iterations
+        assert int(r["routed_cost"][0, h]) <= budget
+        check_sampled_rows(wl, Q[0, h], O[0, h], to_np(r["Kp"][0, h]), to_np(r["Vp"][0, h]), to_np(r["qoff"][0, h]),
+                           to_np(r["koff"][0, h]), to_np(r["perm_q"][0, h]), to_np(r["kbar"][0, h]),
+                           to_np(r["vbar"][0, h]), to_np(r["mask_bits"][0, h]), to_np(r["row_ptr"][0, h]), rng,
+                           n_random=24, what=f"wan step 2 head {h}")
 
 
 def test_full_size_kmeans_labels_bit_exact_wan():

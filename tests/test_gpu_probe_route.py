@@ -61,6 +61,33 @@ def test_probe_scores_match_oracle(name, plain):
             assert int(r["routed_cost"][b, h]) == cost_ref
 
 
+@pytest.mark.parametrize("name", ["mini_video", "mini_d64", "mini_f32_d128", "mini_manyq"])
+@pytest.mark.parametrize("plain", [False, True])
+def test_probe_scores_with_keys_above_every_centroid_logit(name, plain):
+    """Keys whose logit q̄_a.k_j exceeds the row's stabiliser m_a = max_b S̄_ab (outliers far from
+    their cluster's mean): exp(s - m_a) is then large, which is where a streaming evaluation needs
+    its rescaling (Algorithm 1) and where this library's exponent cap (40) would start to matter.
+    The excess is kept well inside the cap and the scores must still be those of Eq. (7) / Eq. (5)."""
+    wl, refs, qbar, kbar, vbar, Kp, Vp, qoff, koff = _stage_inputs(name)
+    scale = orc.scale_of(wl.d)
+    Kp = Kp.clone()
+    Kp[:, :, ::7] *= 4.0  # a power of two: exact in bf16
+    r = sv.probe_route(qbar, kbar, vbar, Kp, Vp, qoff, koff, 0, scale, flags=sv.PROBE_PLAIN if plain else 0)
+    torch.cuda.synchronize()
+    B, H = qbar.shape[:2]
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            ref = refs[b][h]
+            _, s_ref, m = orc.probe_errors(ref["qbar"], ref["kbar"], ref["vbar"], to_np(Kp[b, h]), to_np(Vp[b, h]),
+                                           ref["koff"], scale, value_aware=not plain)
+            nv = wl.N - wl.n_tail
+            excess = (to_np(Kp[b, h])[:nv].astype(np.float64) @ ref["qbar"].astype(np.float64).T * scale).max(0) - m
+            worst = max(worst, float(excess.max()))
+            _check_scores(to_np(r["scores"][b, h]), s_ref)
+    assert 5.0 < worst < 35.0, worst  # the case really has outliers, and none reaches the cap
+
+
 @pytest.mark.parametrize("name", ["tiny", "mini_video_tail"])
 @pytest.mark.parametrize("per_row", [False, True])
 def test_route_bit_exact_from_injected_scores(name, per_row):

@@ -12,3 +12,4 @@ from .generators import (  # noqa: F401
     kmeans_init_indices,
     budget_pairs,
 )
+from .sampling import structural_rows  # noqa: F401
