@@ -14,6 +14,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    *os.environ.get("SVGEAR_HIPCC_FLAGS", "").split(),  # extra flags for experiments, e.g. -DNAME=value
 ]
 
 

@@ -29,6 +29,7 @@ struct AttnArgs {
   const int32_t* sched_bh;
   const int32_t* sched_a;
   const int32_t* sched_row0;
+  const int32_t* sched_rend;  // tile = rows [sched_row0, sched_rend) of query cluster sched_a
   int32_t* sched_x;
   int64_t Nq, Nk;
   int BH, Cq, Ck, max_tiles;

@@ -265,7 +265,7 @@ static int attn_run(const void* qp, const void* kp, const void* vp, svgear_dtype
     SVGEAR_LAUNCH_CHECK();
   }
   AttnArgs a{qp, kp, vp, kbar, vbar, kbar16, vbar16, q_offsets, k_offsets, mask_bits, row_ptr, col_idx,
-             tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr,
+             tile_a, tile_row0, n_tiles, nullptr, nullptr, nullptr, nullptr, nullptr,
              Nq, Nk, BH, Cq, Ck, max_tiles, scale, op, lse, part, tok_perm, q_st, out_st, H};
   if (dt == SVGEAR_F32) {
     dim3 grid(max_tiles, BH);

@@ -465,9 +465,8 @@ attn_bf16_d128_kernel(AttnArgs p) {
   if (claimed < 0) return;
   const int bh = p.sched_bh[claimed], a = p.sched_a[claimed], row0 = p.sched_row0[claimed];
   const int Cq = p.Cq, Ck = p.Ck, R = Cq + 1, Cc = Ck + 1, W = (Cc + 31) / 32;
-  const int32_t* qo = p.q_offsets + (int64_t)bh * (Cq + 2);
   const int32_t* ko = p.k_offsets + (int64_t)bh * (Ck + 2);
-  const int row_end = qo[a + 1];
+  const int row_end = p.sched_rend[claimed];  // the tile's rows are [row0, row_end), all of query cluster a
   const int32_t* rp = p.row_ptr + (int64_t)bh * (R + 1);
   const int32_t* ci = p.col_idx + (int64_t)bh * R * Cc + rp[a];
   const int ne = rp[a + 1] - rp[a];
@@ -923,7 +922,7 @@ __global__ void __launch_bounds__(1024)
 plan_lists_kernel(const int32_t* __restrict__ q_offsets, const int32_t* __restrict__ item_nt,
                   const int32_t* __restrict__ by_rank, int M, int Cq, int BM, int32_t* __restrict__ rank_off,
                   int32_t* __restrict__ sched_bh, int32_t* __restrict__ sched_a, int32_t* __restrict__ sched_row0,
-                  int32_t* __restrict__ sched_x) {
+                  int32_t* __restrict__ sched_rend, int32_t* __restrict__ sched_x) {
   __shared__ int32_t part[1024];
   __shared__ int32_t total[8], first[8];
   const int tid = threadIdx.x, R = Cq + 1;
@@ -967,11 +966,16 @@ plan_lists_kernel(const int32_t* __restrict__ q_offsets, const int32_t* __restri
     const int i = by_rank[r], bh = i / R, a = i % R;
     const int nt = item_nt[i];
     const int base = first[list_of_rank(r)] + rank_off[r];
-    const int q0 = q_offsets[(int64_t)bh * (Cq + 2) + a];
+    const int q0 = q_offsets[(int64_t)bh * (Cq + 2) + a], q1 = q_offsets[(int64_t)bh * (Cq + 2) + a + 1];
+    // The cluster's 32-row wave blocks are dealt evenly to its nt tiles (sizes differ by at most
+    // one block): a cluster of 500 rows becomes two tiles of 8 waves rather than one of 12 and
+    // one of 4, whose lone wave per SIMD would leave the matrix cores idle most of the time.
+    const int blocks = (q1 - q0 + 31) / 32;
     for (int j = 0; j < nt; ++j) {
       sched_bh[base + j] = bh;
       sched_a[base + j] = a;
-      sched_row0[base + j] = q0 + j * BM;
+      sched_row0[base + j] = q0 + 32 * (int)((int64_t)j * blocks / nt);
+      sched_rend[base + j] = min(q1, q0 + 32 * (int)((int64_t)(j + 1) * blocks / nt));
     }
   }
 }
@@ -993,7 +997,7 @@ size_t attn_bf16_lds_bytes(int d, int Ck) {
 size_t plan_d128_workspace(int BH, int Cq, int64_t Nq) {
   const size_t M = (size_t)BH * (Cq + 1);
   const size_t tiles = (size_t)BH * ((size_t)ceil_div(Nq, 32 * kD128Waves) + Cq + 1);
-  return 4 * align_up(M * 4, 256) + 3 * align_up(tiles * 4, 256) + align_up(24 * 4, 256);
+  return 4 * align_up(M * 4, 256) + 4 * align_up(tiles * 4, 256) + align_up(24 * 4, 256);
 }
 
 int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
@@ -1007,6 +1011,7 @@ int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
   int32_t* sched_bh = w.take<int32_t>(tiles);
   int32_t* sched_a = w.take<int32_t>(tiles);
   int32_t* sched_row0 = w.take<int32_t>(tiles);
+  int32_t* sched_rend = w.take<int32_t>(tiles);
   int32_t* sched_x = w.take<int32_t>(24);
   if (!w.ok()) return SVGEAR_ERR_WORKSPACE;
   plan_items_kernel<<<a.BH, 256, 0, s>>>(a.q_offsets, a.k_offsets, a.row_ptr, a.col_idx, a.Cq, a.Ck, BM, item_T, item_nt);
@@ -1014,11 +1019,12 @@ int plan_d128(AttnArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
   plan_rank_kernel<<<(unsigned)ceil_div(M, kRankItems), 256, 0, s>>>(item_T, M, by_rank);
   SVGEAR_LAUNCH_CHECK();
   plan_lists_kernel<<<1, 1024, 0, s>>>(a.q_offsets, item_nt, by_rank, M, a.Cq, BM, rank_off, sched_bh, sched_a, sched_row0,
-                                      sched_x);
+                                      sched_rend, sched_x);
   SVGEAR_LAUNCH_CHECK();
   a.sched_bh = sched_bh;
   a.sched_a = sched_a;
   a.sched_row0 = sched_row0;
+  a.sched_rend = sched_rend;
   a.sched_x = sched_x;
   return SVGEAR_OK;
 }
