@@ -28,6 +28,7 @@ import torch  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CUs x 4 SIMDs x 64 lanes x 2 flop x 2.4 GHz
 # HBM bytes per launch of the fused attention kernel come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled
 # by a 1 GiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0). They are kept in a tracked text file together with the
 # hash of the kernel sources they were measured on; a figure measured on other sources is not reported.
@@ -70,10 +71,13 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense brackets")
     ap.add_argument("--sample-rows", type=int, default=64,
                     help="random output rows per sampled head checked against the oracle (structural rows come on top)")
-    ap.add_argument("--mode", default="layer", choices=["layer", "sweep", "trajectory"],
+    ap.add_argument("--mode", default="layer", choices=["layer", "sweep", "trajectory", "attention-steps"],
                     help="layer: one JSON line for the whole hot path (default); sweep: routed-budget sweep with "
                          "per-stage times and the compensation-only / dense brackets; trajectory: warm-started "
-                         "k-means over denoising steps")
+                         "k-means over denoising steps; attention-steps: the fused attention kernel on synthetic "
+                         "block layouts (equal query clusters of k x 32 rows, equal key clusters), which separates "
+                         "its time per 64-key step from its fixed time per query tile and shows how the step time "
+                         "depends on the number of active waves")
     ap.add_argument("--one-stream", action="store_true",
                     help="profiling aid: run the Q and the K/V call of a stage one after the other on one stream, so "
                          "that a kernel trace shows each kernel's duration when it has the GPU to itself")
@@ -322,6 +326,59 @@ def run_sweep(sv, args, wl, Q, K, V, cq0, ck0):
     print(json.dumps(out))
 
 
+def run_attention_steps(sv):
+    """Kernel-level timing of attn_bf16_d128_kernel on synthetic layouts (bf16, d = 128, 16 heads): every query
+    cluster has 32 k rows (k active waves per tile), every key cluster the same size, each query cluster routes
+    `routed` random key clusters. (1) k = 12, exactly 12 tiles per CU, the routed count varied: a least-squares fit
+    of time per tile against the steps per tile T gives the fixed time per tile and the time per step. (2) a quarter
+    of the key clusters routed, k varied: time per tile-step against the active waves."""
+    dev = torch.device("cuda:0")
+    H, d, Ck = 16, 128, 512
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+
+    def run_case(k, Cq, routed):
+        N = Cq * 32 * k
+        Q, K, V = (torch.randn(1, H, N, d, generator=gen, device=dev).to(torch.bfloat16) for _ in range(3))
+        kbar, vbar = torch.randn(1, H, Ck, d, device=dev), torch.randn(1, H, Ck, d, device=dev)
+        ks = np.full(Ck, N // Ck)
+        ks[: N - ks.sum()] += 1
+        koff = np.concatenate([[0], np.cumsum(ks), [N]]).astype(np.int32)
+        qoff = np.concatenate([np.arange(Cq + 1) * 32 * k, [N]]).astype(np.int32)
+        rng = np.random.default_rng(1000 * k + routed)
+        W = (Ck + 1 + 31) // 32
+        mask = np.zeros((Cq + 1, W * 32), bool)
+        for a in range(Cq):
+            mask[a, rng.choice(Ck, routed, replace=False)] = True
+        bits = np.zeros((Cq + 1, W), np.uint32)
+        for j in range(32):
+            bits |= mask[:, j::32].astype(np.uint32) << np.uint32(j)
+        rp = np.zeros(Cq + 2, np.int32)
+        rp[1:] = np.cumsum(mask[:, : Ck + 1].sum(1))
+        ci = np.zeros((Cq + 1) * (Ck + 1), np.int32)
+        nz = np.concatenate([np.nonzero(mask[a, : Ck + 1])[0] for a in range(Cq + 1)])
+        ci[: len(nz)] = nz
+        rep = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(torch.int32).to(dev)[None, None].expand(
+            1, H, *x.shape).contiguous()
+        meta = [rep(qoff), rep(koff), rep(bits.view(np.int32)), rep(rp), rep(ci)]
+        call = lambda: sv.sparse_attn_comp(Q, K, V, kbar, vbar, *meta, d ** -0.5)
+        call()
+        ms = min(_time_ms(call, reps=1)[0] for _ in range(4))
+        steps = float(np.mean([(int(ks[np.nonzero(mask[a, :Ck])[0]].sum()) + 63) // 64 for a in range(Cq)])) + Ck // 64
+        tiles = H * Cq * ((32 * k + 383) // 384)
+        return {"active_waves": k, "query_clusters": Cq, "routed_key_clusters": routed, "steps_per_tile": steps,
+                "tiles_per_cu": tiles / 256.0, "kernel_ms": ms, "us_per_tile": ms * 1e3 / (tiles / 256.0),
+                "ns_per_tile_step": ms * 1e6 / (tiles / 256.0 * steps)}
+
+    fit_rows = [run_case(12, 192, r) for r in (0, 16, 32, 64, 128, 256)]
+    A = np.array([[1.0, r["steps_per_tile"]] for r in fit_rows])
+    y = np.array([r["us_per_tile"] for r in fit_rows])
+    (a, b), *_ = np.linalg.lstsq(A, y, rcond=None)
+    wave_rows = [run_case(k, 2304 // k, 128) for k in (12, 9, 8, 6, 4, 3, 2, 1)]
+    print(json.dumps({"mode": "attention-steps", "kernel": "attn_bf16_d128_kernel", "heads": H, "key_clusters": Ck,
+                      "fit_us_per_tile": a, "fit_ns_per_step": b * 1e3, "fit_cases": fit_rows, "wave_cases": wave_rows}))
+
+
 def run_trajectory(sv, args, wl):
     """Denoising-trajectory stack: `layers` attention layers x `traj_steps` steps; each step's
     Q/K/V = previous + N(0, 0.05^2) drift (re-rounded to bf16); k-means warm-started from the
@@ -392,6 +449,9 @@ def main():
     if args.mode == "trajectory":
         run_trajectory(sv, args, wl)
         return
+    if args.mode == "attention-steps":
+        run_attention_steps(sv)
+        return
     Q, K, V = make_qkv(wl, dev)
     nv = wl.N - wl.n_tail
     cq0 = torch.empty(wl.B, wl.H, wl.Cq, wl.d, device=dev)
@@ -447,6 +507,8 @@ def main():
             comp_pairs += float((qs[:, None] * ((~m) & (ks[None, :] > 0))).sum())
     attn_flops = 4.0 * wl.d * (routed_pairs + comp_pairs)
     attn_ms = stages["attention"]
+    # bf16: matrix cores; fp32 (one query row per lane on the vector ALUs): the fp32 vector peak
+    peak_tflops = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS
     achieved = attn_flops / (attn_ms * 1e-3) / 1e12
     density = routed_pairs / (wl.B * wl.H * float(wl.N) ** 2)
 
@@ -472,10 +534,11 @@ def main():
         "worst_sampled_row": {"rel_l2": worst_row[1], "row": worst_row[2]},
         "probe_max_exponent_above_row_stabiliser": {"value": excess, "cap": 40.0, "cap_reached": bool(excess > 40.0)},
         "attention_stage": {"ms": attn_ms, "dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12},
-        "roofline": {"bound": "mfma", "kernel": ("attn_bf16_d128_kernel" if wl.d == 128 else "attn_bf16_kernel") if wl.dtype == "bf16"
+        "roofline": {"bound": "mfma" if wl.dtype == "bf16" else "alu",
+                     "kernel": ("attn_bf16_d128_kernel" if wl.d == 128 else "attn_bf16_kernel") if wl.dtype == "bf16"
                      else "attn_f32_kernel",
-                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "achieved": achieved, "peak": peak_tflops, "unit": "TFLOP/s",
+                     "frac": achieved / peak_tflops,
                      "traffic": measured_attention_traffic(wl.name, wl.rho, wl.H),
                      "kernel_source_hash": attention_source_hash(),
                      "algorithmic_flops_per_launch": attn_flops},

@@ -189,3 +189,50 @@ def test_largest_cluster_count_the_abi_accepts():
         c_ref, n_ref = orc.cluster_means(to_np(X[0, 0]), lab_ref, C, before)
         assert np.array_equal(to_np(cnt[0, 0]), n_ref)
         assert np.allclose(to_np(cent[0, 0]), c_ref, atol=2e-5)
+
+
+@pytest.mark.parametrize("name,which", [("mini_video", "k"), ("mini_video", "q"), ("mini_manyk", "k"), ("mini_d64", "k"),
+                                        ("mini_video_tail", "k"), ("mini_manyq", "q")])
+def test_kmeans_later_iterations_bit_exact(name, which):
+    """Iterations after the first (where the library re-assigns only the rows its distance bounds
+    cannot settle, against the centroids near the row's old one): the labels after n iterations
+    must be the oracle's fixed-order assignment to the centroids after n - 1 iterations, which a
+    run of n - 1 iterations reproduces (the library is deterministic)."""
+    wl = get_workload(name)
+    Q, K, V = make_qkv(wl, dev())
+    X, C, tid = (Q, wl.Cq, 0) if which == "q" else (K, wl.Ck, 1)
+    c0 = init_centroids(X, C, wl.seed, tid, wl.n_tail)
+    B, H, N, d = X.shape
+    prev = c0.clone()
+    sv.kmeans(X, prev, 1, wl.n_tail)
+    for n in range(2, 8):
+        cur = c0.clone()
+        labels, counts, _ = sv.kmeans(X, cur, n, wl.n_tail)
+        torch.cuda.synchronize()
+        for b in range(B):
+            for h in range(H):
+                x = to_np(X[b, h])[: N - wl.n_tail]
+                l_ref = orc.kmeans_assign(x, to_np(prev[b, h]))
+                assert np.array_equal(to_np(labels[b, h]), l_ref), f"{name} {which}: labels differ after {n} iterations"
+                c_ref, n_ref = orc.cluster_means(x, l_ref, C, to_np(prev[b, h]))
+                assert np.array_equal(to_np(counts[b, h]), n_ref)
+                assert np.all(np.abs(to_np(cur[b, h]) - c_ref) <= 1e-5 * np.maximum(1.0, np.abs(c_ref)))
+        prev = cur
+
+
+def test_kmeans_many_clusters_several_iterations_bit_exact():
+    """More centroids than one neighbour list holds, tight and overlapping clusters, 5 iterations."""
+    g = torch.Generator(device="cpu").manual_seed(7)
+    n, d, C = 6000, 128, 700
+    centers = torch.randn(90, d, generator=g)
+    X = (centers[torch.randint(0, 90, (n,), generator=g)] + 0.6 * torch.randn(n, d, generator=g)).to(torch.bfloat16)
+    X = X[None, None].to(dev()).contiguous()
+    c0 = X[:, :, torch.randperm(n, generator=g)[:C]].float().contiguous()
+    prev = c0.clone()
+    sv.kmeans(X, prev, 4)
+    cur = c0.clone()
+    labels, counts, _ = sv.kmeans(X, cur, 5)
+    torch.cuda.synchronize()
+    l_ref = orc.kmeans_assign(to_np(X[0, 0]), to_np(prev[0, 0]))
+    assert np.array_equal(to_np(labels[0, 0]), l_ref)
+    assert np.array_equal(to_np(counts[0, 0]), np.bincount(l_ref, minlength=C))
