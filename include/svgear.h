@@ -91,6 +91,14 @@ int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, 
                   float* centroids, float* centroids2, int32_t* labels, int32_t* counts,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* Tuning (host only; results never depend on it). From the second iteration on, a bf16 call
+ * re-assigns only the rows whose distance bounds do not prove that their label stays. With
+ * C >= the value set here each such row is tested against the centroids near its cluster only
+ * (candidate lists from centroid-to-centroid distances); with fewer centroids against all of
+ * them. min_centroids >= 1 sets the threshold for later calls of this process (INT_MAX: never
+ * use lists); min_centroids <= 0 only queries. Returns the previous value (default 513). */
+int svgear_kmeans_list_threshold(int min_centroids);
+
 /* ---------------------------------------------------------------------------------------
  * permute (Motivation, "Structured Redundancy": tokens within each cluster are laid out
  * contiguously so the attention map becomes a grid of blocks).

@@ -21,7 +21,7 @@ USE_GIVEN_SCORES = 4
 
 EXPORTED_SYMBOLS = [
     "svgear_version", "svgear_last_hip_error",
-    "svgear_kmeans_workspace", "svgear_kmeans",
+    "svgear_kmeans_workspace", "svgear_kmeans", "svgear_kmeans_list_threshold",
     "svgear_permute_workspace", "svgear_permute", "svgear_permute_rows",
     "svgear_permute_static_capacity", "svgear_permute_static",
     "svgear_probe_route_workspace", "svgear_probe_route", "svgear_probe_route_top_p",
@@ -138,6 +138,15 @@ def _strides4(t: torch.Tensor):
 
 def _ws(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def kmeans_list_threshold(min_centroids: int = 0) -> int:
+    """svgear_kmeans_list_threshold: sets (>= 1) or queries (<= 0) the number of centroids from which
+    the later k-means iterations use candidate lists; returns the previous value."""
+    lib = load_library()
+    lib.svgear_kmeans_list_threshold.restype = _i
+    lib.svgear_kmeans_list_threshold.argtypes = [_i]
+    return int(lib.svgear_kmeans_list_threshold(int(min_centroids)))
 
 
 def kmeans(x: torch.Tensor, centroids: torch.Tensor, iters: int, n_tail: int = 0,

@@ -120,8 +120,14 @@ __device__ __forceinline__ void async_copy_4B(const void* gptr, uint32_t lds_add
 // chunk_hist: scratch of BH * sort_chunks(N) * (C+1) int32.
 constexpr int kSortChunk = 2048;
 static inline int64_t sort_chunks(int64_t N) { return ceil_div(N, kSortChunk); }
+// tiles (optional, [BH][tile_cap], tile_cap >= N / tile_len + C + 1): the sorted order cut into
+// tiles of at most tile_len positions that never straddle a cluster: tile
+// t = floor(offsets[c] / tile_len) + c + j is positions offsets[c] + tile_len j .. of cluster c, stored
+// as (c, first position, end position, 0); indices no cluster uses hold c = -1.
+// rank (optional, [BH][N]): the position of every token in the sorted order (perm's inverse).
 int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C, int32_t* perm,
-                int32_t* offsets, int32_t* chunk_hist, hipStream_t s);
+                int32_t* offsets, int32_t* chunk_hist, hipStream_t s, int4* tiles = nullptr, int tile_cap = 0,
+                int tile_len = 64, int32_t* rank = nullptr);
 
 
 // Per-head length of the probe's per-key statistic arrays (padded so that 16-byte reads

@@ -15,9 +15,16 @@
 // |filter score - fixed-order score| keeps the filter's label (the fixed-order argmin is
 // provably the same); the few remaining rows are re-assigned by the fp32 kernel, so the
 // labels are always those of the fixed-order definition.
+// From the second iteration on only the rows whose distance bounds (Hamerly's: one upper, one
+// lower bound per row, widened by the centroids' moves) do not prove that the fixed-order label
+// stays are assigned again; with many centroids each such row is tested only against the
+// centroids near its cluster (lists built from centroid-to-centroid distances, with the same
+// kind of proof). Neither changes a label.
 // Update: members are brought into cluster order by the stable counting sort, then summed
 // in a fixed order (interleaved partial sums per cluster, combined in slot order) -- no float
 // atomics, so the centroids are run-to-run deterministic.
+#include <atomic>
+
 #include "common.h"
 
 namespace svgear {
@@ -26,6 +33,14 @@ namespace {
 constexpr int kAssignWaves = 8;                 // 32 rows per wave
 constexpr int kAssignRows = 32 * kAssignWaves;  // rows per workgroup
 constexpr int kCentChunk = 64;                  // centroids per LDS stage (two 32-blocks)
+// per head: [0] rows queued for assign_filter_kernel; as float bits: [1] max |x| of the flagged rows, [2] max |c|^2
+constexpr int kHeadState = 4;
+constexpr int kListMax = 128;                   // longest candidate list of a cluster (longer: every centroid)
+constexpr int kListTile = 64;                   // sorted positions per step of a wave of assign_list_kernel
+constexpr int kListChunk = 4 * kListTile;       // sorted positions per wave (one cluster's)
+// Candidate lists pay when there are many centroids: with fewer than this, testing every
+// centroid (shared through LDS by 256 rows, streaming) costs no more than the lists' gathers.
+std::atomic<int> g_list_min_centroids{513};
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
@@ -39,17 +54,19 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 //    MFMAs with one 16-byte read and a wave reads 1 KB contiguously.
 //  * chl (optional): the bf16 split c = hi + lo + residual, hi = bf16(c), lo = bf16(c - hi), in
 //    the operand order of v_mfma_f32_32x32x16_bf16 (A[i = lane%32][k = 16s + 8(lane/32) + e]):
-//    [blk][piece][s][lane][e], 16 bytes per lane;
-//  * amb_count (optional) is reset for the filter pass.
+//    [blk][piece][s][lane][e], 16 bytes per lane; crow (with chl): the same two pieces row by row,
+//    [c][piece][d], for the kernel that fetches single centroids;
+//  * amb_count, head_state, rmax (optional): the per-iteration counters and maxima are reset.
 __global__ void __launch_bounds__(256)
 prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, float* __restrict__ cperm,
-                      float* __restrict__ cn, bf16_t* __restrict__ chl, int32_t* __restrict__ amb_count,
-                      int32_t* __restrict__ act_count, int32_t* __restrict__ dirty) {
+                      float* __restrict__ cn, bf16_t* __restrict__ chl, bf16_t* __restrict__ crow,
+                      int32_t* __restrict__ amb_count, int32_t* __restrict__ head_state, int32_t* __restrict__ rmax,
+                      int32_t* __restrict__ dirty) {
   const int bh = blockIdx.y;
   const float* cb = cent + (int64_t)bh * C * d;
   const int64_t n = (int64_t)Cpad * d;
   if (amb_count && blockIdx.x == 0 && threadIdx.x == 0) amb_count[bh] = 0;
-  if (act_count && blockIdx.x == 0 && threadIdx.x == 0) act_count[bh] = 0;
+  if (head_state && blockIdx.x == 0 && threadIdx.x < kHeadState) head_state[bh * kHeadState + threadIdx.x] = 0;
   // both operand tables are written 16 bytes per thread from 32 contiguous bytes of a centroid row
   if (chl) {
     const int ksn = d / 16;
@@ -76,6 +93,9 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
       const int64_t base = (int64_t)bh * 2 * n + (((int64_t)blk * 2) * ksn + sidx) * 512 + lane * 8;
       *reinterpret_cast<uint4*>(chl + base) = uint4{hw[0], hw[1], hw[2], hw[3]};
       *reinterpret_cast<uint4*>(chl + base + (int64_t)ksn * 512) = uint4{lw[0], lw[1], lw[2], lw[3]};
+      const int64_t rbase = (int64_t)bh * 2 * n + (int64_t)c * 2 * d + k0;
+      *reinterpret_cast<uint4*>(crow + rbase) = uint4{hw[0], hw[1], hw[2], hw[3]};
+      *reinterpret_cast<uint4*>(crow + rbase + d) = uint4{lw[0], lw[1], lw[2], lw[3]};
     }
   }
   for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n / 4; u += (int64_t)gridDim.x * 256) {
@@ -93,6 +113,7 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
   }
   for (int c = blockIdx.x * 256 + threadIdx.x; c < Cpad; c += gridDim.x * 256) {
     if (dirty) dirty[(int64_t)bh * Cpad + c] = 0;  // no cluster has gained or lost a member yet
+    if (rmax) rmax[(int64_t)bh * Cpad + c] = 0;    // nor has any of its rows been queued
     float acc = INFINITY;
     if (c < C) {
       acc = 0.f;
@@ -257,6 +278,94 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   }
 }
 
+// The same assignment for a short list of rows (the filter's ambiguous ones): with few rows
+// the kernel above leaves most of the chip idle while each of its waves walks every centroid, so
+// here the centroids of a 32-row tile are dealt to the 4 waves of the workgroup (32-blocks
+// round-robin), every wave fetches its operand fragments straight from the table (1 KB
+// contiguous per fetch; no LDS stage, no barrier inside the walk), and the four partial
+// (min, argmin) meet in LDS at the end. Every score is the same chain of matrix-core
+// instructions as above, and ties still go to the lowest index.
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+assign_few_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const float* __restrict__ cperm,
+                  const float* __restrict__ cn, int Cpad, int32_t* __restrict__ labels,
+                  const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
+                  int32_t* __restrict__ dirty) {
+  constexpr int QG = D / 8;  // 16-byte operand groups per 32-block
+  __shared__ float s_best[4][32];
+  __shared__ int s_arg[4][32];
+  const int bh = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t n_rows = row_count[bh];
+  const float* cp = cperm + (int64_t)bh * Cpad * D;
+  const float* cnb = cn + (int64_t)bh * Cpad;
+  for (int64_t tile = blockIdx.x; tile * 32 < n_rows; tile += gridDim.x) {
+    const int64_t pos = tile * 32 + li;
+    const int64_t row = row_list[(int64_t)bh * nv + (pos < n_rows ? pos : n_rows - 1)];
+    float xb[D / 2];
+    load_row_operands<D>(x + head_base(st, bh, H) + row * st.n, lh, xb);
+    float best = INFINITY;
+    int arg = 0;
+    for (int blk = wave; blk < Cpad / 32; blk += 4) {
+      const float* cb = cp + (int64_t)blk * 32 * D + lane * 4;
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+      for (int q0 = 0; q0 < QG; q0 += 8) {  // 8 fetches in flight, then their 32 MFMAs in k order
+        float4 a[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) a[q] = *reinterpret_cast<const float4*>(cb + (q0 + q) * 256);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].x, xb[4 * (q0 + q) + 0], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].y, xb[4 * (q0 + q) + 1], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].z, xb[4 * (q0 + q) + 2], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].w, xb[4 * (q0 + q) + 3], acc, 0, 0, 0);
+        }
+      }
+      // register r is centroid 32 blk + 8(r/4) + 4 lh + r%4, row li
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 n4 = *reinterpret_cast<const float4*>(cnb + 32 * blk + 8 * g + 4 * lh);
+        const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float score = __builtin_fmaf(-2.0f, acc[4 * g + r], nn[r]);
+          const int idx = 32 * blk + 8 * g + 4 * lh + r;
+          if (score < best) { best = score; arg = idx; }
+        }
+      }
+    }
+    const float ob = __shfl_xor(best, 32);
+    const int oa = __shfl_xor(arg, 32);
+    if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+    if (lh == 0) {
+      s_best[wave][li] = best;
+      s_arg[wave][li] = arg;
+    }
+    __syncthreads();
+    if (wave == 0 && lh == 0 && pos < n_rows) {
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float wb = s_best[w][li];
+        const int wa = s_arg[w][li];
+        if (wb < best || (wb == best && wa < arg)) { best = wb; arg = wa; }
+      }
+      if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
+        const int cur = labels[(int64_t)bh * nv + row];
+        if (cur != arg) {
+          dirty[(int64_t)bh * Cpad + cur] = 1;
+          dirty[(int64_t)bh * Cpad + arg] = 1;
+        }
+      }
+      labels[(int64_t)bh * nv + row] = arg;
+    }
+    __syncthreads();  // the LDS slots are written again by the next tile
+  }
+}
+
 // ---- bf16 filter -----------------------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
@@ -282,6 +391,69 @@ __device__ __forceinline__ float fixed_order_error(float X, float Cm) {
   return (D + 2) * 5.9604644775390625e-08f * 1.001f * (Cm * Cm + 2.0f * X * Cm);
 }
 
+// Per-row state between iterations: bnd[row] = (ub, lb), an upper bound of the row's distance
+// to its centroid and a lower bound of its distance to every other centroid; xnorm[row] = |x|_2
+// rounded up.
+//
+// What a filter kernel does with a row once its lanes have ranked the centroids they tested:
+// (best, second, arg) are the lowest and second-lowest approximate score and the position of the
+// lowest seen by THIS lane; the two lanes of a row (lane, lane ^ 32) each saw half of the
+// centroids of every 32-block and are merged here. `positions` (optional) maps a position in the
+// tested list to a centroid index. far_lb: a lower bound of the row's distance to every centroid
+// that was not tested (+inf if all were). cur: the row's present label if the caller knows it
+// (-1: read it). Writes the label if it changes, queues the row for the exact kernel if the
+// margin does not exceed the bound B on the filter's error (see assign_filter_kernel), flags the
+// clusters the row leaves and joins, and stores the row's bounds for the next iterations: with F
+// the distance of a filter score from the real |c|^2 - 2 x.c, the assigned centroid is at most
+// sqrt(best + F + |x|^2) away and every other one at least sqrt(second - F + |x|^2) (tested) or
+// far_lb (not tested). A row whose label the exact kernel decides gets no lower bound (it is
+// assigned again next iteration).
+template <int D>
+__device__ __forceinline__ void settle_row(float best, float second, int arg, bool valid, int64_t row, float X,
+                                           float Cm, float far_lb, const int32_t* __restrict__ positions, int cur,
+                                           int bh, int64_t nv, int Cpad, int32_t* __restrict__ labels,
+                                           int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
+                                           float2* __restrict__ bnd, int32_t* __restrict__ dirty) {
+  constexpr float kappa = 1.52587890625e-05f + (2 * D + 1) * 1.1920928955078125e-07f + D * 5.9604644775390625e-08f;
+  const int lane = threadIdx.x & 63, lh = lane >> 5;
+  const float ob = __shfl_xor(best, 32), os = __shfl_xor(second, 32);
+  const int oa = __shfl_xor(arg, 32);
+  const float lo = fminf(best, ob), hi = fmaxf(best, ob);
+  const float sec = fminf(hi, fminf(second, os));
+  int a = (ob < best || (ob == best && oa < arg)) ? oa : arg;
+  if (lh == 0 && valid) {
+    if (positions) a = positions[a];
+    const float B = 2.0f * X * Cm * kappa + 1.1920928955078125e-07f * (Cm * Cm + 2.0f * X * Cm);
+    if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
+      if (cur < 0) cur = labels[(int64_t)bh * nv + row];
+      if (cur != a) {
+        dirty[(int64_t)bh * Cpad + cur] = 1;
+        dirty[(int64_t)bh * Cpad + a] = 1;
+      }
+    }
+    if (cur != a) labels[(int64_t)bh * nv + row] = a;
+    const bool ambiguous = !(sec - lo > 2.0f * B * 1.0001f);  // also catches NaN / inf margins
+    if (ambiguous) {
+      // one counter update for the ambiguous rows of the wave (the active lanes here)
+      const unsigned long long am = __ballot(1);
+      const int leader = __ffsll((long long)am) - 1;
+      int slot = 0;
+      if (lane == leader) slot = atomicAdd(&amb_count[bh], __popcll(am));
+      slot = __shfl(slot, leader) + __popcll(am & ((1ull << lane) - 1ull));
+      amb_rows[(int64_t)bh * nv + slot] = (int32_t)row;
+    }
+    if (bnd) {
+      const float F = B + fixed_order_error<D>(X, Cm);
+      const float x2_hi = X * X, x2_lo = X * X * 0.9999f;
+      const float u2 = lo + (ambiguous ? 2.0002f * B : 0.f) + F + x2_hi;
+      const float l2 = sec - F + x2_lo;
+      float lbv = (ambiguous || !(l2 > 0.f)) ? 0.f : sqrtf(l2) * 0.999999f;
+      lbv = fminf(lbv, fmaxf(far_lb, 0.f));
+      bnd[(int64_t)bh * nv + row] = make_float2(sqrtf(fmaxf(u2, 0.f)) * 1.000001f, lbv);
+    }
+  }
+}
+
 // Approximate scores s~(c) = fma(-2, x.hi_c + x.lo_c, |c|^2) on bf16 MFMAs, with the best and
 // second-best kept per row. With X = |x|_2, Cm = max_c |c|_2 and d the head dimension,
 //   |x.c(filter) - x.c(fixed order)| <= X Cm (2^-16 + (2d+1) 2^-23 + d 2^-24) =: X Cm kappa
@@ -291,14 +463,15 @@ __device__ __forceinline__ float fixed_order_error(float X, float Cm) {
 // so two scores differ from their fixed-order values by at most
 //   B = 2 X Cm kappa + 2^-23 (Cm^2 + 2 X Cm).
 // If second - best > 2B the fixed-order argmin is the filter's argmin; otherwise the row is
-// queued for the exact kernel.
+// queued for the exact kernel. With row_list != nullptr only the rows listed there
+// (row_count[kHeadState bh] of them, in any order) are assigned.
 template <int D>
 __global__ void __launch_bounds__(64 * kFilterWaves)
 assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, const bf16_t* __restrict__ chl,
                      const float* __restrict__ cn, float* __restrict__ xnorm, int C, int Cpad,
                      int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
                      const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
-                     float* __restrict__ ub, float* __restrict__ lb, int32_t* __restrict__ dirty) {
+                     float2* __restrict__ bnd, int32_t* __restrict__ dirty) {
   constexpr int KSN = D / 16;
   constexpr int CHUNK_BYTES = kCentChunk * D * 2 * 2;  // 64 centroids, hi and lo pieces
   constexpr int COPIES = CHUNK_BYTES / 1024 / kFilterCopyWaves;
@@ -307,8 +480,7 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   float* cns = reinterpret_cast<float*>(smem + 2 * CHUNK_BYTES);  // [Cpad] |c|^2 of every centroid
   float* red = cns + Cpad;                                        // [64 * kFilterWaves]
   const int bh = blockIdx.y;
-  // with a row list only the listed rows (row_count[bh] of them, in any order) are assigned
-  const int64_t n_rows = row_list ? row_count[bh] : nv;
+  const int64_t n_rows = row_list ? row_count[bh * kHeadState] : nv;
   if ((int64_t)blockIdx.x * kFilterRows >= n_rows) return;
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -345,33 +517,29 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
     for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(*reinterpret_cast<const uint4*>(xr + 16 * s + 8 * lh));
   }
   SVGEAR_WAIT_VMCNT(0);
-  // |x|_2 of the rows, rounded up: the first pass (every row, no row list) computes it from the
-  // operands it holds - each lane squares its half of the row, the halves meet across lane^32 -
-  // and stores it for the later passes and the bounds; an fp32 sum of d squares in any order
-  // is within d 2^-24 of the exact one, which the factor covers
+  // |x|_2 of the rows, rounded up, computed from the operands the lane holds - each lane squares
+  // its half of the row, the halves meet across lane^32 - and stored for the later iterations;
+  // an fp32 sum of d squares in any order is within d 2^-24 of the exact one, which the factor
+  // covers
   float xn[2];
 #pragma unroll
   for (int rs = 0; rs < 2; ++rs) {
-    if (row_list) {
-      xn[rs] = xnorm[(int64_t)bh * nv + rows[rs]];
-    } else {
-      float acc = 0.f;
+    float acc = 0.f;
 #pragma unroll
-      for (int s = 0; s < KSN; ++s) {
-        union { bf16x8 b; uint4 u; } c;
-        c.b = bx[rs][s];
-        const uint32_t w[4] = {c.u.x, c.u.y, c.u.z, c.u.w};
+    for (int s = 0; s < KSN; ++s) {
+      union { bf16x8 b; uint4 u; } c;
+      c.b = bx[rs][s];
+      const uint32_t w[4] = {c.u.x, c.u.y, c.u.z, c.u.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
-          acc = __builtin_fmaf(lo, lo, acc);
-          acc = __builtin_fmaf(hi, hi, acc);
-        }
+      for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+        acc = __builtin_fmaf(lo, lo, acc);
+        acc = __builtin_fmaf(hi, hi, acc);
       }
-      acc += __shfl_xor(acc, 32);
-      xn[rs] = sqrtf(acc) * 1.00002f;
-      if (lh == 0 && valid[rs]) xnorm[(int64_t)bh * nv + rows[rs]] = xn[rs];
     }
+    acc += __shfl_xor(acc, 32);
+    xn[rs] = sqrtf(acc) * 1.00002f;
+    if (!row_list && lh == 0 && valid[rs]) xnorm[(int64_t)bh * nv + rows[rs]] = xn[rs];
   }
 
   const unsigned char* cp = reinterpret_cast<const unsigned char*>(chl + (int64_t)bh * 2 * Cpad * D);
@@ -463,51 +631,10 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
     // block 2ch+2 (next chunk) into A while ranking block 2ch+1 from B
     step(2 * ch + 1, ch + 1 < nchunks, accB0, accB1, accA0, accA1);
   }
-  constexpr float kappa = 1.52587890625e-05f + (2 * D + 1) * 1.1920928955078125e-07f + D * 5.9604644775390625e-08f;
 #pragma unroll
-  for (int rs = 0; rs < 2; ++rs) {
-    // merge the two lanes of a row (each saw half of the centroids)
-    const float ob = __shfl_xor(best[rs], 32), os = __shfl_xor(second[rs], 32);
-    const int oa = __shfl_xor(arg[rs], 32);
-    const float lo = fminf(best[rs], ob), hi = fmaxf(best[rs], ob);
-    const float sec = fminf(hi, fminf(second[rs], os));
-    const int a = (ob < best[rs] || (ob == best[rs] && oa < arg[rs])) ? oa : arg[rs];
-    if (lh == 0 && valid[rs]) {
-      const float X = xn[rs];
-      const float B = 2.0f * X * Cm * kappa + 1.1920928955078125e-07f * (Cm * Cm + 2.0f * X * Cm);
-      if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
-        const int cur = labels[(int64_t)bh * nv + rows[rs]];
-        if (cur != a) {
-          dirty[(int64_t)bh * Cpad + cur] = 1;
-          dirty[(int64_t)bh * Cpad + a] = 1;
-        }
-      }
-      labels[(int64_t)bh * nv + rows[rs]] = a;
-      const bool ambiguous = !(sec - lo > 2.0f * B * 1.0001f);  // also catches NaN / inf margins
-      if (ambiguous) {
-        // one counter update for the ambiguous rows of the wave (the active lanes here)
-        const unsigned long long am = __ballot(1);
-        const int leader = __ffsll((long long)am) - 1;
-        int slot = 0;
-        if (lane == leader) slot = atomicAdd(&amb_count[bh], __popcll(am));
-        slot = __shfl(slot, leader) + __popcll(am & ((1ull << lane) - 1ull));
-        amb_rows[(int64_t)bh * nv + slot] = (int32_t)rows[rs];
-      }
-      if (ub) {
-        // Distance bounds for the next iterations (see bounds_update_kernel): with F the
-        // distance of a filter score from the real |c|^2 - 2 x.c, the assigned centroid is at
-        // most sqrt(best + F + |x|^2) away and every other one at least
-        // sqrt(second - F + |x|^2). A row whose label the exact kernel decides gets no lower
-        // bound (it is assigned again next iteration).
-        const float F = B + fixed_order_error<D>(X, Cm);
-        const float x2_hi = X * X, x2_lo = X * X * 0.9999f;
-        const float u2 = lo + (ambiguous ? 2.0002f * B : 0.f) + F + x2_hi;
-        const float l2 = sec - F + x2_lo;
-        ub[(int64_t)bh * nv + rows[rs]] = sqrtf(fmaxf(u2, 0.f)) * 1.000001f;
-        lb[(int64_t)bh * nv + rows[rs]] = (ambiguous || !(l2 > 0.f)) ? 0.f : sqrtf(l2) * 0.999999f;
-      }
-    }
-  }
+  for (int rs = 0; rs < 2; ++rs)
+    settle_row<D>(best[rs], second[rs], arg[rs], valid[rs], rows[rs], xn[rs], Cm, INFINITY, nullptr, -1, bh, nv, Cpad,
+                  labels, amb_rows, amb_count, bnd, dirty);
 }
 
 constexpr int kBoundRows = 8;  // rows per thread of bounds_update_kernel
@@ -555,68 +682,360 @@ __device__ __forceinline__ void head_stats(const float* __restrict__ cn, const f
   cm2_out = cm2; d1_out = d1; d2_out = d2; a1_out = a1;
 }
 
-// Which rows need a new assignment (Hamerly's bounds). ub[row] bounds the distance of the row
-// to its centroid from above, lb[row] its distance to every other centroid from below, both
-// for the centroids of the previous assignment. The centroids have since moved by at most
+// Which rows need a new assignment (Hamerly's bounds). bnd[row] holds ub, an upper bound of the
+// row's distance to its centroid, and lb, a lower bound of its distance to every other centroid,
+// both for the centroids of the previous assignment. The centroids have since moved by at most
 // drift[c]; by the triangle inequality the row's centroid is now at most u = ub + drift[label]
 // away and every other at least l = lb - (largest drift among the others). If l^2 - u^2
 // exceeds twice the error E of a fixed-order fp32 score, the fixed-order argmin is the old
 // label, strictly, so the row is skipped and keeps its label with the widened bounds;
-// otherwise it is queued for the filter kernel. Skipping never changes a label, so the
-// result is the same as assigning every row in every iteration.
-template <int D>
+// otherwise it is flagged. Skipping never changes a label, so the result is the same as
+// assigning every row in every iteration.
+// LISTS = false: the flagged rows are queued (act_rows, counted in head_state[kHeadState bh])
+// for assign_filter_kernel.
+// LISTS = true: they are left to assign_list_kernel: prow, indexed by the row's position in the
+// sorted order of the previous iteration, holds the row's index (-1 for a skipped row); per
+// cluster the kernel records rmax = the largest u among its flagged rows (the radius the
+// cluster's candidate list is built for; non-negative floats order like their bit patterns),
+// per head the largest |x| among the flagged rows and max |c|^2.
+template <int D, bool LISTS>
 __global__ void __launch_bounds__(256)
 bounds_update_kernel(const int32_t* __restrict__ labels, const float* __restrict__ xnorm,
                      const float* __restrict__ cn, const float* __restrict__ drift, int C, int Cpad, int64_t nv,
-                     float* __restrict__ ub, float* __restrict__ lb, int32_t* __restrict__ act_rows,
-                     int32_t* __restrict__ act_count) {
+                     float2* __restrict__ bnd, int32_t* __restrict__ act_rows, const int32_t* __restrict__ rank,
+                     int32_t* __restrict__ prow, int32_t* __restrict__ rmax, int32_t* __restrict__ head_state) {
   const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float cm2, d1, d2;
   int a1;
   head_stats(cn + (int64_t)bh * Cpad, drift + (int64_t)bh * Cpad, C, cm2, d1, d2, a1);
   const float Cm = sqrtf(cm2) * 1.00002f;
+  if (LISTS && blockIdx.x == 0 && tid == 0) head_state[bh * kHeadState + 2] = __float_as_int(cm2);
 
   // kBoundRows rows per thread, 256 apart (a launch of one-row threads is bound by the rate at
   // which workgroups start, not by memory)
+  float xmax = 0.f;
   unsigned qmask = 0;
 #pragma unroll
   for (int j = 0; j < kBoundRows; ++j) {
     const int64_t row = ((int64_t)blockIdx.x * kBoundRows + j) * 256 + tid;
     if (row < nv) {
       const int a = labels[(int64_t)bh * nv + row];
+      const float2 st = bnd[(int64_t)bh * nv + row];
       const float X = xnorm[(int64_t)bh * nv + row];
-      const float u = (ub[(int64_t)bh * nv + row] + drift[(int64_t)bh * Cpad + a]) * 1.000001f;
-      const float l = (lb[(int64_t)bh * nv + row] - (a == a1 ? d2 : d1)) * 0.999999f;
+      const float u = (st.x + drift[(int64_t)bh * Cpad + a]) * 1.000001f;
+      const float l = (st.y - (a == a1 ? d2 : d1)) * 0.999999f;
       const float E = fixed_order_error<D>(X, Cm);
       const bool keep = l > u && (l - u) * (l + u) > 2.002f * E;  // false for NaN
+      bnd[(int64_t)bh * nv + row] = make_float2(u, l > 0.f ? l : 0.f);
       if (!keep) qmask |= 1u << j;
-      ub[(int64_t)bh * nv + row] = u;
-      lb[(int64_t)bh * nv + row] = l > 0.f ? l : 0.f;
+      if constexpr (LISTS) {
+        prow[(int64_t)bh * nv + rank[(int64_t)bh * nv + row]] = keep ? -1 : (int32_t)row;
+        if (!keep) {
+          const int ubits = __float_as_int(u);
+          // (the plain read only saves atomics: most rows find a radius that already covers them)
+          if (ubits > rmax[(int64_t)bh * Cpad + a]) atomicMax(&rmax[(int64_t)bh * Cpad + a], ubits);
+          xmax = fmaxf(xmax, X);
+        }
+      }
     }
   }
-  // queue the rows of this workgroup with one counter update: exclusive scan of the per-thread
-  // counts (wave shuffles, then the four wave totals)
-  __shared__ int s_cnt[4], s_base;
-  const int cnt = __popc(qmask);
-  int incl = cnt;
+  if constexpr (LISTS) {
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(incl, o);
-    if (lane >= o) incl += t;
-  }
-  if (lane == 63) s_cnt[wave] = incl;
-  __syncthreads();
-  if (tid == 0) {
-    const int total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-    s_base = total ? atomicAdd(&act_count[bh], total) : 0;
-  }
-  __syncthreads();
-  int pos = s_base + incl - cnt;
-  for (int w = 0; w < wave; ++w) pos += s_cnt[w];
+    for (int o = 32; o > 0; o >>= 1) xmax = fmaxf(xmax, __shfl_xor(xmax, o));
+    if (lane == 0 && xmax > 0.f) atomicMax(&head_state[bh * kHeadState + 1], __float_as_int(xmax));
+  } else {
+    // queue the rows of this workgroup with one counter update: exclusive scan of the per-thread
+    // counts (wave shuffles, then the four wave totals)
+    __shared__ int s_cnt[4], s_base;
+    const int cnt = __popc(qmask);
+    int incl = cnt;
 #pragma unroll
-  for (int j = 0; j < kBoundRows; ++j)
-    if (qmask & (1u << j))
-      act_rows[(int64_t)bh * nv + pos++] = (int32_t)(((int64_t)blockIdx.x * kBoundRows + j) * 256 + tid);
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    if (lane == 63) s_cnt[wave] = incl;
+    __syncthreads();
+    if (tid == 0) {
+      const int total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+      s_base = total ? atomicAdd(&head_state[bh * kHeadState], total) : 0;
+    }
+    __syncthreads();
+    int pos = s_base + incl - cnt;
+    for (int w = 0; w < wave; ++w) pos += s_cnt[w];
+#pragma unroll
+    for (int j = 0; j < kBoundRows; ++j)
+      if (qmask & (1u << j))
+        act_rows[(int64_t)bh * nv + pos++] = (int32_t)(((int64_t)blockIdx.x * kBoundRows + j) * 256 + tid);
+  }
+}
+
+// Candidate lists. For cluster a whose flagged rows are all within R of its centroid, a
+// centroid c at distance d from centroid a cannot be the fixed-order argmin of any of those rows
+// if (d - R)^2 - R^2 = d (d - 2R) exceeds twice the error E of a fixed-order fp32 score: the
+// row is at least d - R from c and at most R from a, so in real numbers c's score exceeds a's
+// by more than 2E and its fixed-order score is strictly larger. Every other centroid joins
+// the list (ascending index; a itself always does). dout[a] is a lower bound of the distance
+// from centroid a to the nearest centroid left out (+inf if none): the rows' lower bounds need
+// it. A list longer than kListMax is replaced by "every centroid" (nlen = -1).
+// The centroid-to-centroid products run on the bf16 matrix cores from the operand table of the
+// filter (c = hi + lo + a residual below 2^-16 |c|), which serves as A operand (centroid c of a
+// 32-block = row lane % 32) and as B operand (cluster a = column lane % 32) alike: a.c ~
+// hi.hi + hi.lo + lo.hi, and d^2 = |a|^2 + |c|^2 - 2 a.c is lowered by 1.2e-4 (|a|^2 + |c|^2), more
+// than the split residuals, the dropped lo.lo term and the fp32 roundings together. One wave per
+// 32 clusters walks all 32-blocks of centroids; a lane owns one cluster (column) and 16
+// centroids of the block, so the ordered append needs only the partner lane's counts.
+template <int D>
+__global__ void __launch_bounds__(256)
+nlist_kernel(const bf16_t* __restrict__ chl, const float* __restrict__ cn, int C, int Cpad,
+             const int32_t* __restrict__ rmax, const int32_t* __restrict__ head_state, int32_t* __restrict__ nlist,
+             int32_t* __restrict__ nlen, float* __restrict__ dout) {
+  constexpr int KSN = D / 16;
+  const int bh = blockIdx.y, lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+  const int ab = blockIdx.x * 4 + (threadIdx.x >> 6);  // block of 32 clusters of this wave
+  if (ab * 32 >= C) return;
+  const int a = ab * 32 + li;
+  const bf16_t* tab = chl + (int64_t)bh * 2 * Cpad * D;
+  const float* cnb = cn + (int64_t)bh * Cpad;
+  bf16x8 bhi[KSN], blo[KSN];
+#pragma unroll
+  for (int s = 0; s < KSN; ++s) {
+    bhi[s] = as_bf16x8(*reinterpret_cast<const uint4*>(tab + ((int64_t)(ab * 2) * KSN + s) * 512 + lane * 8));
+    blo[s] = as_bf16x8(*reinterpret_cast<const uint4*>(tab + ((int64_t)(ab * 2 + 1) * KSN + s) * 512 + lane * 8));
+  }
+  const float cna = a < C ? cnb[a] : 0.f;
+  const float r2 = a < C ? 2.0f * __int_as_float(rmax[(int64_t)bh * Cpad + a]) * 1.000001f : 0.f;
+  const float Cm = sqrtf(__int_as_float(head_state[bh * kHeadState + 2])) * 1.00002f;
+  const float E2 = 2.002f * fixed_order_error<D>(__int_as_float(head_state[bh * kHeadState + 1]), Cm);
+  int32_t* out = nlist + ((int64_t)bh * C + (a < C ? a : 0)) * kListMax;
+  int run = 0;
+  float dmin = INFINITY;
+  for (int cb = 0; cb * 32 < C; ++cb) {
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KSN; ++s) {
+      const bf16_t* frag = tab + ((int64_t)(cb * 2) * KSN + s) * 512 + lane * 8;  // hi piece; lo: KSN fragments on
+      const bf16x8 ahi = as_bf16x8(*reinterpret_cast<const uint4*>(frag));
+      const bf16x8 alo = as_bf16x8(*reinterpret_cast<const uint4*>(frag + (int64_t)KSN * 512));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, bhi[s], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, blo[s], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, bhi[s], acc, 0, 0, 0);
+    }
+    // register r is centroid 32 cb + 8 (r/4) + 4 lh + r%4, cluster a
+    unsigned keep = 0;
+    int cnt[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 n4 = *reinterpret_cast<const float4*>(cnb + 32 * cb + 8 * g + 4 * lh);
+      const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
+      cnt[g] = 0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int c = 32 * cb + 8 * g + 4 * lh + r;
+        const float nsum = cna + nn[r];
+        const float dd2 = nsum - 2.0f * acc[4 * g + r] - 1.2e-4f * nsum;  // lower bound of |a - c|^2
+        const float d = sqrtf(fmaxf(dd2, 0.f)) * 0.999999f;               // lower bound of |a - c|
+        const bool out_c = d > r2 && d * (d - r2) * 0.9999f > E2;         // false for NaN: kept
+        const bool k = c < C && (!out_c || c == a);
+        if (c < C && !k) dmin = fminf(dmin, d);
+        if (k) {
+          keep |= 1u << (4 * g + r);
+          ++cnt[g];
+        }
+      }
+    }
+    // ascending order inside the block: group g of the lower lane half (centroids 8g .. 8g+3),
+    // then group g of the upper half (8g+4 .. 8g+7)
+    const int mine = cnt[0] | (cnt[1] << 4) | (cnt[2] << 8) | (cnt[3] << 12);
+    const int theirs = __shfl_xor(mine, 32);
+    int pos = run;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int tg = (theirs >> (4 * g)) & 15;
+      if (lh) pos += tg;  // the lower half's group comes first
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (keep & (1u << (4 * g + r))) {
+          if (pos < kListMax && a < C) out[pos] = 32 * cb + 8 * g + 4 * lh + r;
+          ++pos;
+        }
+      if (!lh) pos += tg;
+    }
+    run = pos;  // both lanes of a cluster arrive at the same total
+  }
+  dmin = fminf(dmin, __shfl_xor(dmin, 32));
+  if (lh == 0 && a < C) {
+    nlen[(int64_t)bh * C + a] = run <= kListMax ? run : -1;
+    dout[(int64_t)bh * C + a] = run <= kListMax ? dmin : INFINITY;
+  }
+}
+
+// Later iterations: the flagged rows against the candidate list of the cluster they are in -- a
+// centroid outside the list provably has a larger fixed-order score than the row's old
+// centroid, so the argmin over the list is the argmin over all centroids. A few clusters (wide
+// ones, whose radius reaches most centroids) have no list (nlen < 0): their flagged rows are
+// only queued here, for assign_filter_kernel, which tests every centroid and shares the
+// centroids among 256 rows. One wave takes a chunk of at most kListChunk positions of ONE cluster in
+// the sorted order (chunk table of sort_labels), 64 positions per step. Lists are short (a
+// handful to a few dozen centroids once the clustering settles), so there is nothing to share
+// between waves: no LDS, no barrier. What bounds the kernel is the number of cache lines its
+// fetches touch (every row and every candidate lies somewhere else), so
+//  * a list of at most 32 candidates is fetched once per wave and stays in registers;
+//  * a lane reads half a row / half a piece of "its" candidate (position lane % 32 of the list's
+//    32-block) as whole cache lines: the contraction index is permuted (the filter's scores are
+//    approximate and their error bound holds for any order of the additions), in k-step s lane
+//    (i, h) holds dims D/2 h + 8 s .. + 7 of centroid / row i;
+//  * rows that are not flagged are not fetched, and nothing of a flagged row's state is read:
+//    every 4 bytes read or written at a row's index cost a whole memory transaction, as much as
+//    a quarter of the row itself. |x| is computed again from the row, the row's old upper bound
+//    is replaced by the cluster's radius, and which rows are flagged comes in position order;
+//  * the chain of dependent fetches is three long (tile -> rows and list -> operands), and the
+//    rows of the next step are looked up while this step's are ranked.
+template <int D>
+__global__ void __launch_bounds__(64)
+assign_list_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, const bf16_t* __restrict__ crow,
+                   const float* __restrict__ cn, int C, int Cpad, int32_t* __restrict__ labels,
+                   int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
+                   const int32_t* __restrict__ prow, const int4* __restrict__ tiles, int tile_cap,
+                   const int32_t* __restrict__ rmax, const int32_t* __restrict__ nlist,
+                   const int32_t* __restrict__ nlen, const float* __restrict__ dout,
+                   int32_t* __restrict__ head_state, int32_t* __restrict__ act_rows, float2* __restrict__ bnd,
+                   int32_t* __restrict__ dirty) {
+  constexpr int KSN = D / 16;
+  const int bh = blockIdx.y, lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+  const int4 tile = tiles[(int64_t)bh * tile_cap + blockIdx.x];
+  const int a_old = tile.x, p_begin = tile.y, p_end = tile.z;
+  if (a_old < 0) return;
+  const int n_list = nlen[(int64_t)bh * C + a_old];
+  if (n_list < 0) {  // no list: queue the flagged rows
+    for (int p = p_begin + lane; p < p_end; p += 64) {
+      const int r = prow[(int64_t)bh * nv + p];
+      if (r >= 0) {
+        const unsigned long long am = __ballot(1);
+        const int leader = __ffsll((long long)am) - 1;
+        int slot = 0;
+        if (lane == leader) slot = atomicAdd(&head_state[bh * kHeadState], __popcll(am));
+        slot = __shfl(slot, leader) + __popcll(am & ((1ull << lane) - 1ull));
+        act_rows[(int64_t)bh * nv + slot] = r;
+      }
+    }
+    return;
+  }
+  // a centroid outside the list is at least |a_old - c| - |x - a_old| away from a flagged row x of
+  // the cluster, and the list was built for |x - a_old| <= rmax
+  const float far = dout[(int64_t)bh * C + a_old] * 0.99999f -
+                    __int_as_float(rmax[(int64_t)bh * Cpad + a_old]) * 1.000001f;
+  const float Cm = sqrtf(__int_as_float(head_state[bh * kHeadState + 2])) * 1.00002f;
+  const int nblk = (n_list + 31) / 32;
+  const int32_t* lst = nlist + ((int64_t)bh * C + a_old) * kListMax;
+  const bf16_t* tab = crow + (int64_t)bh * 2 * Cpad * D;
+  const float* cnb = cn + (int64_t)bh * Cpad;
+
+  // this lane's candidate of block g (both lane halves hold the same one): operands and |c|^2
+  bf16x8 av[2 * KSN];
+  float cnv;
+  auto fetch_candidates = [&](int g) {
+    // (the entry is fetched whether or not the list reaches it, so that the fetch does not wait for
+    // the list's length; an entry beyond the length is whatever the memory holds and is not used)
+    const int entry = lst[32 * g + li];
+    const int ci = 32 * g + li < n_list ? entry : -1;
+    const int cc = ci < 0 ? 0 : ci;  // padding: any centroid's bits, its |c|^2 entry is +inf
+    cnv = ci < 0 ? INFINITY : cnb[cc];
+    const bf16_t* src = tab + (int64_t)cc * 2 * D + (D / 2) * lh;
+#pragma unroll
+    for (int i = 0; i < 2 * KSN; ++i)  // hi piece (k-steps 0 .. KSN-1), then lo piece
+      av[i] = as_bf16x8(*reinterpret_cast<const uint4*>(src + (i / KSN) * D + 8 * (i % KSN)));
+  };
+  // rows of the step at positions p .. p + 63 (row set rs, lane li: position p + 32 rs + li) and
+  // whether they are flagged
+  auto fetch_rows = [&](int p, int64_t (&rows)[2], int (&flag)[2]) {
+#pragma unroll
+    for (int rs = 0; rs < 2; ++rs) {
+      const int pos = p + 32 * rs + li;
+      const int r = pos < p_end ? prow[(int64_t)bh * nv + pos] : -1;
+      rows[rs] = r < 0 ? 0 : r;
+      flag[rs] = r >= 0;
+    }
+  };
+
+  int64_t rows[2], rows_next[2];
+  int flag[2], flag_next[2];
+  fetch_rows(p_begin, rows, flag);
+  fetch_candidates(0);
+  for (int p = p_begin; p < p_end; p += kListTile) {
+    const bool more = p + kListTile < p_end;
+    if (more) fetch_rows(p + kListTile, rows_next, flag_next);
+    const bool valid[2] = {flag[0] != 0, flag[1] != 0};
+    if (__any(valid[0] || valid[1])) {  // else nothing flagged in this step (whole wave)
+      bf16x8 bx[2][KSN];
+      float xn[2];
+#pragma unroll
+      for (int rs = 0; rs < 2; ++rs) {
+#pragma unroll
+        for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(uint4{0u, 0u, 0u, 0u});
+        if (valid[rs]) {
+          const bf16_t* xr = x + head_base(st, bh, H) + rows[rs] * st.n + (D / 2) * lh;
+#pragma unroll
+          for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(*reinterpret_cast<const uint4*>(xr + 8 * s));
+        }
+        // |x|_2 rounded up, as in assign_filter_kernel
+        float acc = 0.f;
+#pragma unroll
+        for (int s = 0; s < KSN; ++s) {
+          union { bf16x8 b; uint4 u; } c;
+          c.b = bx[rs][s];
+          const uint32_t w[4] = {c.u.x, c.u.y, c.u.z, c.u.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+            acc = __builtin_fmaf(lo, lo, acc);
+            acc = __builtin_fmaf(hi, hi, acc);
+          }
+        }
+        acc += __shfl_xor(acc, 32);
+        xn[rs] = sqrtf(acc) * 1.00002f;
+      }
+      float best[2] = {INFINITY, INFINITY}, second[2] = {INFINITY, INFINITY};
+      int arg[2] = {0, 0};
+      for (int g = 0; g < nblk; ++g) {
+        if (nblk > 1) fetch_candidates(g);  // (a single block is already in registers)
+        f32x16 acc0, acc1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2 * KSN; ++i) {
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bx[0][i % KSN], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bx[1][i % KSN], acc1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          // register r is the candidate at position 32 g + 8(r/4) + 4 lh + r%4 of the list
+          const int k = 8 * (r >> 2) + 4 * lh + (r & 3);
+          const float nn = __shfl(cnv, k);
+          const int idx = 32 * g + k;
+          const float s0 = __builtin_fmaf(-2.0f, acc0[r], nn);
+          const float s1 = __builtin_fmaf(-2.0f, acc1[r], nn);
+          second[0] = __builtin_amdgcn_fmed3f(s0, best[0], second[0]);
+          second[1] = __builtin_amdgcn_fmed3f(s1, best[1], second[1]);
+          if (s0 < best[0]) { best[0] = s0; arg[0] = idx; }
+          if (s1 < best[1]) { best[1] = s1; arg[1] = idx; }
+        }
+      }
+#pragma unroll
+      for (int rs = 0; rs < 2; ++rs)
+        settle_row<D>(best[rs], second[rs], arg[rs], valid[rs], rows[rs], xn[rs], Cm, far, lst, a_old, bh, nv, Cpad,
+                      labels, amb_rows, amb_count, bnd, dirty);
+    }
+    if (more) {
+#pragma unroll
+      for (int rs = 0; rs < 2; ++rs) {
+        rows[rs] = rows_next[rs];
+        flag[rs] = flag_next[rs];
+      }
+    }
+  }
 }
 
 // Mean of the members of one cluster. A row is covered by LPR lanes of 16 bytes each; the
@@ -778,20 +1197,28 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
   float* cperm = ws.take<float>((size_t)BH * Cpad * D);
   constexpr bool kFilter = sizeof(T) == 2;  // bf16 input: filter on bf16 MFMAs, then exact on the ambiguous rows
   bf16_t* chl = kFilter ? ws.take<bf16_t>((size_t)BH * 2 * Cpad * D) : nullptr;
-  float* xnorm = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
+  bf16_t* crow = kFilter ? ws.take<bf16_t>((size_t)BH * 2 * Cpad * D) : nullptr;
   int32_t* amb_rows = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
   int32_t* amb_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
   const int P = means_parts(nv, C);
   float* partial = P > 1 ? ws.take<float>((size_t)BH * C * P * D) : nullptr;
-  // row skipping between iterations (bf16 input): distance bounds, centroid moves, row queue
-  float* ub = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
-  float* lb = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
+  // row skipping between iterations (bf16 input): distance bounds and flags per row, centroid
+  // moves, per-cluster radii and candidate lists, the tile table of the sorted order
+  const bool use_lists = kFilter && C >= g_list_min_centroids.load(std::memory_order_relaxed);
+  const int tile_cap = (int)(nv / kListChunk) + C + 1;
+  float2* bnd = kFilter ? ws.take<float2>((size_t)BH * nv) : nullptr;
+  float* xnorm = kFilter ? ws.take<float>((size_t)BH * nv) : nullptr;
+  int32_t* rank = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
+  int32_t* prow = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
   int32_t* act_rows = kFilter ? ws.take<int32_t>((size_t)BH * nv) : nullptr;
-  int32_t* act_count = kFilter ? ws.take<int32_t>((size_t)BH) : nullptr;
-  if (kFilter) ws.take<float>((size_t)BH * C * D);  // (reserved)
+  int32_t* head_state = kFilter ? ws.take<int32_t>((size_t)BH * kHeadState) : nullptr;
   float* drift = kFilter ? ws.take<float>((size_t)BH * Cpad) : nullptr;
-  if (kFilter) ws.take<float>((size_t)BH * 4);  // (reserved)
+  int32_t* rmax = kFilter ? ws.take<int32_t>((size_t)BH * Cpad) : nullptr;
   int32_t* dirty = kFilter ? ws.take<int32_t>((size_t)BH * Cpad) : nullptr;
+  int32_t* nlist = kFilter ? ws.take<int32_t>((size_t)BH * C * kListMax) : nullptr;
+  int32_t* nlen = kFilter ? ws.take<int32_t>((size_t)BH * C) : nullptr;
+  float* dout = kFilter ? ws.take<float>((size_t)BH * C) : nullptr;
+  int4* tiles = kFilter ? ws.take<int4>((size_t)BH * tile_cap) : nullptr;
   if (!ws.ok()) return SVGEAR_ERR_WORKSPACE;
   const size_t lds = 2 * (size_t)kCentChunk * D * 4 + 2 * kCentChunk * sizeof(float);
   auto assign = assign_mfma_kernel<T, D>;
@@ -819,27 +1246,51 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
     return SVGEAR_OK;
   };
   for (int it = 0; it < iters; ++it) {
-    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, amb_count, act_count, dirty);
+    prep_centroids_kernel<<<gp, 256, 0, s>>>(cent, C, Cpad, D, cperm, cn, chl, crow, amb_count, head_state, rmax,
+                                             dirty);
     SVGEAR_LAUNCH_CHECK();
     if constexpr (kFilter) {
-      // first iteration: every row; later ones: only the rows whose bounds do not prove that
-      // their label stays
-      if (it > 0) {
-        bounds_update_kernel<D><<<dim3((unsigned)ceil_div(nv, 256 * kBoundRows), BH), 256, 0, s>>>(
-            labels, xnorm, cn, drift, C, Cpad, nv, ub, lb, act_rows, act_count);
+      const dim3 gf((unsigned)ceil_div(nv, kFilterRows), BH), gb((unsigned)ceil_div(nv, 256 * kBoundRows), BH);
+      const bf16_t* xb = reinterpret_cast<const bf16_t*>(x);
+      if (it == 0) {
+        // every row against every centroid
+        assign_filter_kernel<D><<<gf, 64 * kFilterWaves, lds_f, s>>>(
+            xb, st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count, nullptr, nullptr, bnd, nullptr);
+        SVGEAR_LAUNCH_CHECK();
+      } else {
+        // only the rows whose bounds do not prove that their label stays
+        if (use_lists) {
+          // ... each against the centroids near its cluster
+          bounds_update_kernel<D, true><<<gb, 256, 0, s>>>(labels, xnorm, cn, drift, C, Cpad, nv, bnd, act_rows, rank,
+                                                           prow, rmax, head_state);
+          SVGEAR_LAUNCH_CHECK();
+          nlist_kernel<D><<<dim3((unsigned)ceil_div(C, 128), BH), 256, 0, s>>>(chl, cn, C, Cpad, rmax, head_state,
+                                                                               nlist, nlen, dout);
+          SVGEAR_LAUNCH_CHECK();
+          assign_list_kernel<D><<<dim3((unsigned)tile_cap, BH), 64, 0, s>>>(
+              xb, st, H, nv, crow, cn, C, Cpad, labels, amb_rows, amb_count, prow, tiles, tile_cap, rmax, nlist, nlen,
+              dout, head_state, act_rows, bnd, dirty);
+          SVGEAR_LAUNCH_CHECK();
+        } else {
+          bounds_update_kernel<D, false><<<gb, 256, 0, s>>>(labels, xnorm, cn, drift, C, Cpad, nv, bnd, act_rows,
+                                                            nullptr, nullptr, nullptr, head_state);
+          SVGEAR_LAUNCH_CHECK();
+        }
+        // the queued rows (all flagged rows, or those of the clusters without a list) against
+        // every centroid; the grid covers every row, workgroups beyond the queue's length leave
+        // at once
+        assign_filter_kernel<D><<<gf, 64 * kFilterWaves, lds_f, s>>>(
+            xb, st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count, act_rows, head_state, bnd, dirty);
         SVGEAR_LAUNCH_CHECK();
       }
-      assign_filter_kernel<D><<<dim3((unsigned)ceil_div(nv, kFilterRows), BH), 64 * kFilterWaves, lds_f, s>>>(
-          reinterpret_cast<const bf16_t*>(x), st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count,
-          it > 0 ? act_rows : nullptr, it > 0 ? act_count : nullptr, ub, lb, it > 0 ? dirty : nullptr);
-      SVGEAR_LAUNCH_CHECK();
-      assign<<<dim3((ga.x + 3) / 4, BH), 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, amb_rows,
-                                                                      amb_count, it > 0 ? dirty : nullptr);
+      assign_few_kernel<T, D><<<dim3((unsigned)ceil_div(nv, 32 * 8), BH), 256, 0, s>>>(
+          x, st, H, nv, cperm, cn, Cpad, labels, amb_rows, amb_count, it > 0 ? dirty : nullptr);
     } else {
       assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, nullptr, nullptr, nullptr);
     }
     SVGEAR_LAUNCH_CHECK();
-    int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s);
+    int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s, use_lists ? tiles : nullptr, tile_cap,
+                         kListChunk, use_lists ? rank : nullptr);
     if (rc != SVGEAR_OK) return rc;
     rc = update(x, cent, counts, (kFilter && it > 0) ? dirty : nullptr, drift);
     if (rc != SVGEAR_OK) return rc;
@@ -856,21 +1307,28 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
 
 using namespace svgear;
 
+extern "C" int svgear_kmeans_list_threshold(int min_centroids) {
+  if (min_centroids <= 0) return g_list_min_centroids.load(std::memory_order_relaxed);
+  return g_list_min_centroids.exchange(min_centroids, std::memory_order_relaxed);
+}
+
 extern "C" size_t svgear_kmeans_workspace(int B, int H, int64_t N, int d, int C) {
   if (B <= 0 || H <= 0 || N <= 0 || C <= 0 || d <= 0) return 0;
   const size_t BH = (size_t)B * H;
   const size_t Cpad = align_up(C, kCentChunk);
   return align_up(BH * sort_chunks(N) * (C + 1) * 4, 256) + align_up(BH * N * 4, 256) +
          align_up(BH * (C + 2) * 4, 256) + align_up(BH * Cpad * 4, 256) + align_up(BH * Cpad * d * 4, 256) +
-         // bf16 filter: hi/lo operand tables, row norms, ambiguous-row list and counter
-         align_up(BH * 2 * Cpad * d * 2, 256) + 2 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256) +
+         // bf16 filter: hi/lo operand tables (two layouts), ambiguous-row list and counter
+         2 * align_up(BH * 2 * Cpad * d * 2, 256) + align_up(BH * N * 4, 256) + align_up(BH * 4, 256) +
          // partial sums of the split centroid update
          (means_parts(N, C) > 1 ? align_up(BH * C * means_parts(N, C) * d * 4, 256) : 0) +
-         // row skipping: two bounds and the row queue per row, counters, previous centroids, their moves
-         3 * align_up(BH * N * 4, 256) + align_up(BH * 4, 256) + align_up(BH * C * d * 4, 256) +
-         align_up(BH * Cpad * 4, 256) + align_up(BH * 16, 256) +
-         // membership-changed flag per cluster
-         align_up(BH * Cpad * 4, 256);
+         // row skipping: per row two bounds, the norm, the sorted position, the flagged-row table and
+         // the queue; per-head maxima, centroid moves, radii,
+         // membership-changed flags, candidate lists with their lengths and outer distances, chunk table
+         align_up(BH * N * 8, 256) + 4 * align_up(BH * N * 4, 256) +
+         align_up(BH * kHeadState * 4, 256) + 3 * align_up(BH * Cpad * 4, 256) +
+         align_up(BH * C * kListMax * 4, 256) + 2 * align_up(BH * C * 4, 256) +
+         align_up(BH * (N / kListChunk + C + 1) * 16, 256);
 }
 
 extern "C" int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, int64_t N,

@@ -40,7 +40,7 @@ hist_kernel(const int32_t* __restrict__ labels, int64_t N, int64_t nv, int C, in
 // Turns per-chunk histograms into per-chunk start positions and writes the offsets.
 __global__ void __launch_bounds__(kThreads)
 scan_kernel(int32_t* __restrict__ chunk_hist, int64_t N, int C, int nchunks,
-            int32_t* __restrict__ offsets) {
+            int32_t* __restrict__ offsets, int4* __restrict__ tiles, int tile_cap, int tile_len) {
   extern __shared__ int32_t tot[];  // C+1 totals, then C+1 exclusive offsets
   int32_t* offs = tot + (C + 1);
   const int bh = blockIdx.x;
@@ -106,6 +106,19 @@ scan_kernel(int32_t* __restrict__ chunk_hist, int64_t N, int C, int nchunks,
     }
   }
   if (threadIdx.x == 0) o[C + 1] = (int32_t)N;
+  if (tiles) {  // tiles of the clusters (see sort_labels in common.h)
+    int4* ta = tiles + (int64_t)bh * tile_cap;
+    for (int c = threadIdx.x; c < C; c += kThreads) {
+      const int start = offs[c] / tile_len + c, nt = (tot[c] + tile_len - 1) / tile_len;
+      const int next = c + 1 < C ? offs[c + 1] / tile_len + c + 1 : tile_cap;
+      const int end = offs[c] + tot[c];
+      for (int j = 0; j < nt; ++j) {
+        const int p0 = offs[c] + j * tile_len;
+        ta[start + j] = make_int4(c, p0, p0 + tile_len < end ? p0 + tile_len : end, 0);
+      }
+      for (int j = start + nt; j < next; ++j) ta[j] = make_int4(-1, 0, 0, 0);
+    }
+  }
 }
 
 // Stable placement: tokens of a chunk are taken 256 at a time; inside a wave the rank of a
@@ -114,7 +127,7 @@ scan_kernel(int32_t* __restrict__ chunk_hist, int64_t N, int C, int nchunks,
 // order), so equal labels keep ascending token order without any atomic.
 __global__ void __launch_bounds__(kThreads)
 scatter_kernel(const int32_t* __restrict__ labels, int64_t N, int64_t nv, int C, int nchunks,
-               const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ perm) {
+               const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ perm, int32_t* __restrict__ rank_out) {
   extern __shared__ int32_t base[];  // C+1 next free position per label
   const int bh = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -142,6 +155,7 @@ scatter_kernel(const int32_t* __restrict__ labels, int64_t N, int64_t nv, int C,
       if (wave == w && valid) {
         const int b = base[my];
         out[b + rank] = (int32_t)i;
+        if (rank_out) rank_out[(int64_t)bh * N + i] = b + rank;
         if (rank == total - 1) base[my] = b + total;  // issued after every lane's read of base
       }
       __syncthreads();
@@ -185,7 +199,8 @@ bool strides_ok(const int64_t st[3], size_t es, const void* p) {
 }  // namespace
 
 int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C, int32_t* perm,
-                int32_t* offsets, int32_t* chunk_hist, hipStream_t s) {
+                int32_t* offsets, int32_t* chunk_hist, hipStream_t s, int4* tiles, int tile_cap, int tile_len,
+                int32_t* rank) {
   const int nchunks = (int)sort_chunks(N);
   const int64_t nv = N - n_tail;
   dim3 grid(nchunks, BH);
@@ -195,10 +210,12 @@ int sort_labels(const int32_t* labels, int BH, int64_t N, int64_t n_tail, int C,
   SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(scan_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)(2 * (C + 1) * sizeof(int32_t))));
-  scan_kernel<<<BH, kThreads, 2 * (C + 1) * sizeof(int32_t), s>>>(chunk_hist, N, C, nchunks, offsets);
+  if (tiles && (tile_len < 1 || tile_cap < (int)(N / tile_len) + C + 1)) return SVGEAR_ERR_INVALID;
+  scan_kernel<<<BH, kThreads, 2 * (C + 1) * sizeof(int32_t), s>>>(chunk_hist, N, C, nchunks, offsets, tiles, tile_cap,
+                                                                  tile_len);
   SVGEAR_LAUNCH_CHECK();
   scatter_kernel<<<grid, kThreads, (C + 1) * sizeof(int32_t), s>>>(labels, N, nv, C, nchunks,
-                                                                            chunk_hist, perm);
+                                                                            chunk_hist, perm, rank);
   SVGEAR_LAUNCH_CHECK();
   return SVGEAR_OK;
 }

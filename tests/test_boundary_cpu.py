@@ -34,6 +34,17 @@ def test_version_and_error_state(lib):
     assert lib.svgear_last_hip_error() == 0
 
 
+def test_kmeans_list_threshold_sets_and_queries(lib):
+    lib.svgear_kmeans_list_threshold.restype = ctypes.c_int
+    lib.svgear_kmeans_list_threshold.argtypes = [ctypes.c_int]
+    default = lib.svgear_kmeans_list_threshold(0)
+    assert default == 513
+    assert lib.svgear_kmeans_list_threshold(7) == default
+    assert lib.svgear_kmeans_list_threshold(-3) == 7      # query only
+    assert lib.svgear_kmeans_list_threshold(default) == 7
+    assert lib.svgear_kmeans_list_threshold(0) == default
+
+
 def test_workspace_queries_are_monotone(lib):
     a = lib.svgear_kmeans_workspace(1, 1, 4096, 64, 32)
     b = lib.svgear_kmeans_workspace(1, 40, 75600, 128, 500)

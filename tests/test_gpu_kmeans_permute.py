@@ -10,6 +10,18 @@ from helpers import dev, to_np, init_centroids
 
 pytestmark = pytest.mark.gpu
 
+NEVER = 2**31 - 1
+
+
+@pytest.fixture(params=["lists", "every_centroid"])
+def later_iterations_mode(request):
+    """Both ways the library re-assigns rows after the first iteration, whatever the number of
+    centroids: against candidate lists (threshold 1) and against every centroid."""
+    from paper_2603_08982_amd.binding import kmeans_list_threshold
+    before = kmeans_list_threshold(1 if request.param == "lists" else NEVER)
+    yield request.param
+    kmeans_list_threshold(before)
+
 
 def _lockstep(X, C, iters, n_tail=0, seed=0, tensor_id=0, X2=None):
     """Each iteration: GPU starts from the oracle's centroids; labels must be bit-exact and
@@ -60,7 +72,7 @@ def test_kmeans_lockstep_other_shapes(name):
     _lockstep(K, wl.Ck, 2, seed=wl.seed, tensor_id=1, X2=V)
 
 
-def test_kmeans_free_running_matches_oracle():
+def test_kmeans_free_running_matches_oracle(later_iterations_mode):
     wl = get_workload("tiny")
     Q, K, V = make_qkv(wl, dev())
     cent = init_centroids(K, wl.Ck, 0, 1)
@@ -193,7 +205,7 @@ def test_largest_cluster_count_the_abi_accepts():
 
 @pytest.mark.parametrize("name,which", [("mini_video", "k"), ("mini_video", "q"), ("mini_manyk", "k"), ("mini_d64", "k"),
                                         ("mini_video_tail", "k"), ("mini_manyq", "q")])
-def test_kmeans_later_iterations_bit_exact(name, which):
+def test_kmeans_later_iterations_bit_exact(name, which, later_iterations_mode):
     """Iterations after the first (where the library re-assigns only the rows its distance bounds
     cannot settle, against the centroids near the row's old one): the labels after n iterations
     must be the oracle's fixed-order assignment to the centroids after n - 1 iterations, which a
@@ -220,7 +232,7 @@ def test_kmeans_later_iterations_bit_exact(name, which):
         prev = cur
 
 
-def test_kmeans_many_clusters_several_iterations_bit_exact():
+def test_kmeans_many_clusters_several_iterations_bit_exact(later_iterations_mode):
     """More centroids than one neighbour list holds, tight and overlapping clusters, 5 iterations."""
     g = torch.Generator(device="cpu").manual_seed(7)
     n, d, C = 6000, 128, 700
