@@ -38,6 +38,7 @@ constexpr int kHeadState = 4;
 constexpr int kListMax = 128;                   // longest candidate list of a cluster (longer: every centroid)
 constexpr int kListTile = 64;                   // sorted positions per step of a wave of assign_list_kernel
 constexpr int kListChunk = 4 * kListTile;       // sorted positions per wave (one cluster's)
+constexpr int kMaxCentroids = 8192;             // most centroids per head the entry point accepts
 // Candidate lists pay when there are many centroids: with fewer than this, testing every
 // centroid (shared through LDS by 256 rows, streaming) costs no more than the lists' gathers.
 std::atomic<int> g_list_min_centroids{513};
@@ -113,7 +114,7 @@ prep_centroids_kernel(const float* __restrict__ cent, int C, int Cpad, int d, fl
   }
   for (int c = blockIdx.x * 256 + threadIdx.x; c < Cpad; c += gridDim.x * 256) {
     if (dirty) dirty[(int64_t)bh * Cpad + c] = 0;  // no cluster has gained or lost a member yet
-    if (rmax) rmax[(int64_t)bh * Cpad + c] = 0;    // nor has any of its rows been queued
+    if (rmax) rmax[(int64_t)bh * Cpad + c] = 0;    // nor has any of its rows been flagged
     float acc = INFINITY;
     if (c < C) {
       acc = 0.f;
@@ -727,7 +728,6 @@ bounds_update_kernel(const int32_t* __restrict__ labels, const float* __restrict
       const float E = fixed_order_error<D>(X, Cm);
       const bool keep = l > u && (l - u) * (l + u) > 2.002f * E;  // false for NaN
       bnd[(int64_t)bh * nv + row] = make_float2(u, l > 0.f ? l : 0.f);
-      if (!keep) qmask |= 1u << j;
       if constexpr (LISTS) {
         prow[(int64_t)bh * nv + rank[(int64_t)bh * nv + row]] = keep ? -1 : (int32_t)row;
         if (!keep) {
@@ -737,6 +737,7 @@ bounds_update_kernel(const int32_t* __restrict__ labels, const float* __restrict
           xmax = fmaxf(xmax, X);
         }
       }
+      if (!LISTS && !keep) qmask |= 1u << j;
     }
   }
   if constexpr (LISTS) {
@@ -775,48 +776,55 @@ bounds_update_kernel(const int32_t* __restrict__ labels, const float* __restrict
 // if (d - R)^2 - R^2 = d (d - 2R) exceeds twice the error E of a fixed-order fp32 score: the
 // row is at least d - R from c and at most R from a, so in real numbers c's score exceeds a's
 // by more than 2E and its fixed-order score is strictly larger. Every other centroid joins
-// the list (ascending index; a itself always does). dout[a] is a lower bound of the distance
-// from centroid a to the nearest centroid left out (+inf if none): the rows' lower bounds need
-// it. A list longer than kListMax is replaced by "every centroid" (nlen = -1).
+// the list (a itself always does). dout[a] is a lower bound of the distance from centroid a to
+// the nearest centroid left out (+inf if none): the rows' lower bounds need it. A list longer
+// than kListMax is dropped (nlen = -1: the cluster's rows are tested against every centroid).
 // The centroid-to-centroid products run on the bf16 matrix cores from the operand table of the
 // filter (c = hi + lo + a residual below 2^-16 |c|), which serves as A operand (centroid c of a
 // 32-block = row lane % 32) and as B operand (cluster a = column lane % 32) alike: a.c ~
 // hi.hi + hi.lo + lo.hi, and d^2 = |a|^2 + |c|^2 - 2 a.c is lowered by 1.2e-4 (|a|^2 + |c|^2), more
-// than the split residuals, the dropped lo.lo term and the fp32 roundings together. One wave per
-// 32 clusters walks all 32-blocks of centroids; a lane owns one cluster (column) and 16
-// centroids of the block, so the ordered append needs only the partner lane's counts.
+// than the split residuals, the dropped lo.lo term and the fp32 roundings together.
+// One workgroup per 32 clusters; its 4 waves take the 32-blocks of centroids round-robin. A
+// lane owns one cluster (column) and 16 centroids of a block. First pass: which centroids stay
+// (16 bits per lane and block, kept in LDS) and how many; then every wave knows where its part of
+// each list starts (wave order, inside a wave ascending centroid index: the order is fixed,
+// and no result depends on it -- equal approximate scores send a row to the exact kernel);
+// second pass: the entries are written.
 template <int D>
 __global__ void __launch_bounds__(256)
 nlist_kernel(const bf16_t* __restrict__ chl, const float* __restrict__ cn, int C, int Cpad,
              const int32_t* __restrict__ rmax, const int32_t* __restrict__ head_state, int32_t* __restrict__ nlist,
              int32_t* __restrict__ nlen, float* __restrict__ dout) {
   constexpr int KSN = D / 16;
+  __shared__ uint16_t s_keep[kMaxCentroids / 32][64];
+  __shared__ int s_cnt[4][32];
+  __shared__ float s_dmin[4][32];
   const int bh = blockIdx.y, lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
-  const int ab = blockIdx.x * 4 + (threadIdx.x >> 6);  // block of 32 clusters of this wave
-  if (ab * 32 >= C) return;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ab = blockIdx.x;  // block of 32 clusters
   const int a = ab * 32 + li;
   const bf16_t* tab = chl + (int64_t)bh * 2 * Cpad * D;
   const float* cnb = cn + (int64_t)bh * Cpad;
   bf16x8 bhi[KSN], blo[KSN];
 #pragma unroll
   for (int s = 0; s < KSN; ++s) {
-    bhi[s] = as_bf16x8(*reinterpret_cast<const uint4*>(tab + ((int64_t)(ab * 2) * KSN + s) * 512 + lane * 8));
-    blo[s] = as_bf16x8(*reinterpret_cast<const uint4*>(tab + ((int64_t)(ab * 2 + 1) * KSN + s) * 512 + lane * 8));
+    const bf16_t* frag = tab + ((int64_t)(ab * 2) * KSN + s) * 512 + lane * 8;  // hi piece; lo: KSN fragments on
+    bhi[s] = as_bf16x8(*reinterpret_cast<const uint4*>(frag));
+    blo[s] = as_bf16x8(*reinterpret_cast<const uint4*>(frag + (int64_t)KSN * 512));
   }
   const float cna = a < C ? cnb[a] : 0.f;
   const float r2 = a < C ? 2.0f * __int_as_float(rmax[(int64_t)bh * Cpad + a]) * 1.000001f : 0.f;
   const float Cm = sqrtf(__int_as_float(head_state[bh * kHeadState + 2])) * 1.00002f;
   const float E2 = 2.002f * fixed_order_error<D>(__int_as_float(head_state[bh * kHeadState + 1]), Cm);
-  int32_t* out = nlist + ((int64_t)bh * C + (a < C ? a : 0)) * kListMax;
-  int run = 0;
+  int mine = 0;  // entries of cluster a this lane contributes
   float dmin = INFINITY;
-  for (int cb = 0; cb * 32 < C; ++cb) {
+  for (int cb = wave; cb * 32 < C; cb += 4) {
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
     for (int s = 0; s < KSN; ++s) {
-      const bf16_t* frag = tab + ((int64_t)(cb * 2) * KSN + s) * 512 + lane * 8;  // hi piece; lo: KSN fragments on
+      const bf16_t* frag = tab + ((int64_t)(cb * 2) * KSN + s) * 512 + lane * 8;
       const bf16x8 ahi = as_bf16x8(*reinterpret_cast<const uint4*>(frag));
       const bf16x8 alo = as_bf16x8(*reinterpret_cast<const uint4*>(frag + (int64_t)KSN * 512));
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, bhi[s], acc, 0, 0, 0);
@@ -825,12 +833,10 @@ nlist_kernel(const bf16_t* __restrict__ chl, const float* __restrict__ cn, int C
     }
     // register r is centroid 32 cb + 8 (r/4) + 4 lh + r%4, cluster a
     unsigned keep = 0;
-    int cnt[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const float4 n4 = *reinterpret_cast<const float4*>(cnb + 32 * cb + 8 * g + 4 * lh);
       const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
-      cnt[g] = 0;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int c = 32 * cb + 8 * g + 4 * lh + r;
@@ -840,35 +846,49 @@ nlist_kernel(const bf16_t* __restrict__ chl, const float* __restrict__ cn, int C
         const bool out_c = d > r2 && d * (d - r2) * 0.9999f > E2;         // false for NaN: kept
         const bool k = c < C && (!out_c || c == a);
         if (c < C && !k) dmin = fminf(dmin, d);
-        if (k) {
-          keep |= 1u << (4 * g + r);
-          ++cnt[g];
-        }
+        if (k) keep |= 1u << (4 * g + r);
       }
     }
-    // ascending order inside the block: group g of the lower lane half (centroids 8g .. 8g+3),
-    // then group g of the upper half (8g+4 .. 8g+7)
-    const int mine = cnt[0] | (cnt[1] << 4) | (cnt[2] << 8) | (cnt[3] << 12);
-    const int theirs = __shfl_xor(mine, 32);
-    int pos = run;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int tg = (theirs >> (4 * g)) & 15;
-      if (lh) pos += tg;  // the lower half's group comes first
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (keep & (1u << (4 * g + r))) {
-          if (pos < kListMax && a < C) out[pos] = 32 * cb + 8 * g + 4 * lh + r;
-          ++pos;
-        }
-      if (!lh) pos += tg;
-    }
-    run = pos;  // both lanes of a cluster arrive at the same total
+    s_keep[cb][lane] = (uint16_t)keep;
+    mine += __popc(keep);
   }
+  mine += __shfl_xor(mine, 32);
   dmin = fminf(dmin, __shfl_xor(dmin, 32));
-  if (lh == 0 && a < C) {
-    nlen[(int64_t)bh * C + a] = run <= kListMax ? run : -1;
-    dout[(int64_t)bh * C + a] = run <= kListMax ? dmin : INFINITY;
+  if (lh == 0) {
+    s_cnt[wave][li] = mine;
+    s_dmin[wave][li] = dmin;
+  }
+  __syncthreads();
+  int run = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) run += s_cnt[w][li];
+    total += s_cnt[w][li];
+    dmin = fminf(dmin, s_dmin[w][li]);
+  }
+  if (a < C && total <= kListMax) {  // (a list that is dropped is not written either)
+    int32_t* out = nlist + ((int64_t)bh * C + a) * kListMax;
+    for (int cb = wave; cb * 32 < C; cb += 4) {
+      // (each lane reads back what it wrote itself, and its partner's after the barrier above)
+      const unsigned keep = s_keep[cb][lane], theirs = s_keep[cb][lane ^ 32];
+      // inside the block ascending: group g of the lower lane half (centroids 8g .. 8g+3), then
+      // group g of the upper half (8g+4 .. 8g+7)
+      int pos = run;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int tg = __popc((theirs >> (4 * g)) & 15u);
+        if (lh) pos += tg;  // the lower half's group comes first
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (keep & (1u << (4 * g + r))) out[pos++] = 32 * cb + 8 * g + 4 * lh + r;
+        if (!lh) pos += tg;
+      }
+      run = pos;  // both lanes of a cluster arrive at the same total
+    }
+  }
+  if (wave == 0 && lh == 0 && a < C) {
+    nlen[(int64_t)bh * C + a] = total <= kListMax ? total : -1;
+    dout[(int64_t)bh * C + a] = total <= kListMax ? dmin : INFINITY;
   }
 }
 
@@ -909,18 +929,30 @@ assign_list_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, 
   const int a_old = tile.x, p_begin = tile.y, p_end = tile.z;
   if (a_old < 0) return;
   const int n_list = nlen[(int64_t)bh * C + a_old];
-  if (n_list < 0) {  // no list: queue the flagged rows
-    for (int p = p_begin + lane; p < p_end; p += 64) {
-      const int r = prow[(int64_t)bh * nv + p];
-      if (r >= 0) {
-        const unsigned long long am = __ballot(1);
-        const int leader = __ffsll((long long)am) - 1;
-        int slot = 0;
-        if (lane == leader) slot = atomicAdd(&head_state[bh * kHeadState], __popcll(am));
-        slot = __shfl(slot, leader) + __popcll(am & ((1ull << lane) - 1ull));
-        act_rows[(int64_t)bh * nv + slot] = r;
-      }
+  if (n_list < 0) {  // no list: queue the flagged rows (all fetches first, then one counter update)
+    int r[kListChunk / 64];
+#pragma unroll
+    for (int j = 0; j < kListChunk / 64; ++j) {
+      const int p = p_begin + 64 * j + lane;
+      r[j] = p < p_end ? prow[(int64_t)bh * nv + p] : -1;
     }
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < kListChunk / 64; ++j) mine += r[j] >= 0;
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    const int total = __shfl(incl, 63);
+    if (total == 0) return;
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&head_state[bh * kHeadState], total);
+    int slot = __shfl(base, 0) + incl - mine;
+#pragma unroll
+    for (int j = 0; j < kListChunk / 64; ++j)
+      if (r[j] >= 0) act_rows[(int64_t)bh * nv + slot++] = r[j];
     return;
   }
   // a centroid outside the list is at least |a_old - c| - |x - a_old| away from a flagged row x of
@@ -1264,7 +1296,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
           bounds_update_kernel<D, true><<<gb, 256, 0, s>>>(labels, xnorm, cn, drift, C, Cpad, nv, bnd, act_rows, rank,
                                                            prow, rmax, head_state);
           SVGEAR_LAUNCH_CHECK();
-          nlist_kernel<D><<<dim3((unsigned)ceil_div(C, 128), BH), 256, 0, s>>>(chl, cn, C, Cpad, rmax, head_state,
+          nlist_kernel<D><<<dim3((unsigned)ceil_div(C, 32), BH), 256, 0, s>>>(chl, cn, C, Cpad, rmax, head_state,
                                                                                nlist, nlen, dout);
           SVGEAR_LAUNCH_CHECK();
           assign_list_kernel<D><<<dim3((unsigned)tile_cap, BH), 64, 0, s>>>(
@@ -1336,7 +1368,7 @@ extern "C" int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int
                              float* centroids2, int32_t* labels, int32_t* counts, void* ws, size_t ws_bytes,
                              void* stream) {
   if (!x || !xstride || !centroids || !labels || !counts || B <= 0 || H <= 0 || N <= 0 || n_tail < 0 ||
-      n_tail >= N || C <= 0 || C > N - n_tail || C > 8192 || iters < 1 || N > INT32_MAX / 2 ||
+      n_tail >= N || C <= 0 || C > N - n_tail || C > kMaxCentroids || iters < 1 || N > INT32_MAX / 2 ||
       (d != 64 && d != 128) || (dt != SVGEAR_F32 && dt != SVGEAR_BF16) || ((x2 == nullptr) != (centroids2 == nullptr)))
     return SVGEAR_ERR_INVALID;
   const size_t es = esize(dt);
