@@ -201,6 +201,16 @@ def test_largest_cluster_count_the_abi_accepts():
         c_ref, n_ref = orc.cluster_means(to_np(X[0, 0]), lab_ref, C, before)
         assert np.array_equal(to_np(cnt[0, 0]), n_ref)
         assert np.allclose(to_np(cent[0, 0]), c_ref, atol=2e-5)
+    # three iterations in one call (candidate lists over 256 blocks of centroids from the second
+    # on): the labels are the fixed-order assignment to the centroids two iterations leave
+    prev = init.clone()
+    sv.kmeans(X, prev, 2)
+    cur = init.clone()
+    lab, cnt, _ = sv.kmeans(X, cur, 3)
+    torch.cuda.synchronize()
+    lab_ref = orc.kmeans_assign(to_np(X[0, 0]), to_np(prev[0, 0]))
+    assert np.array_equal(to_np(lab[0, 0]), lab_ref)
+    assert np.array_equal(to_np(cnt[0, 0]), np.bincount(lab_ref, minlength=C))
 
 
 @pytest.mark.parametrize("name,which", [("mini_video", "k"), ("mini_video", "q"), ("mini_manyk", "k"), ("mini_d64", "k"),
