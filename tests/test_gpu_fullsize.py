@@ -202,13 +202,14 @@ def test_full_size_kmeans_labels_bit_exact_wan():
         assert np.all(np.abs(to_np(vbar[0, h])[ne] - v_ref[ne]) <= 1e-5 * np.maximum(1.0, np.abs(v_ref[ne])))
 
 
-@pytest.mark.parametrize("which", ["q", "k"])
-def test_full_size_kmeans_later_iterations_bit_exact_wan(which):
+@pytest.mark.parametrize("name,which", [("wan", "q"), ("wan", "k"), ("wan_c300", "k")])
+def test_full_size_kmeans_later_iterations_bit_exact(name, which):
     """Labels after 6 iterations at the Wan2.2 shape equal the oracle's fixed-order assignment
     against the centroids after 5 iterations (the library is deterministic, so a 5-iteration
     run reproduces them). From the second iteration on the library re-assigns only the rows
-    its distance bounds cannot settle; a wrongly skipped row would show up here."""
-    wl = get_workload("wan")
+    its distance bounds cannot settle - with the 1000 key centroids of wan_c300 against the
+    candidate lists of their clusters; a wrongly skipped row or centroid would show up here."""
+    wl = get_workload(name)
     heads = [0, wl.H - 1]
     Q, K, V = make_qkv(wl, dev(), heads=heads)
     X, C, tensor_id = (Q, wl.Cq, 0) if which == "q" else (K, wl.Ck, 1)
