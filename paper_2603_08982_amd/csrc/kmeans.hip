@@ -383,6 +383,7 @@ constexpr int kFilterWaves = 4;
 constexpr int kFilterCopyWaves = 32 % kFilterWaves == 0 ? kFilterWaves : 4;
 constexpr int kFilterRowsPerWave = 64;  // two 32-row operand sets share every centroid fragment
 constexpr int kFilterRows = kFilterWaves * kFilterRowsPerWave;
+constexpr int kFilterGroups = 8;  // row groups per workgroup when every centroid fits the two LDS stages
 
 // Distance of a fixed-order fp32 score fma(-2, x.c, |c|^2) (both sums fmaf chains over d
 // terms) from the real number |c|^2 - 2 x.c, for |x| <= X and |c| <= Cm: d 2^-24 relative on
@@ -466,8 +467,8 @@ __device__ __forceinline__ void settle_row(float best, float second, int arg, bo
 // If second - best > 2B the fixed-order argmin is the filter's argmin; otherwise the row is
 // queued for the exact kernel. With row_list != nullptr only the rows listed there
 // (row_count[kHeadState bh] of them, in any order) are assigned.
-template <int D>
-__global__ void __launch_bounds__(64 * kFilterWaves)
+template <int D, bool RESIDENT>
+__global__ void __launch_bounds__(64 * kFilterWaves) __attribute__((amdgpu_waves_per_eu(2)))
 assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv, const bf16_t* __restrict__ chl,
                      const float* __restrict__ cn, float* __restrict__ xnorm, int C, int Cpad,
                      int32_t* __restrict__ labels, int32_t* __restrict__ amb_rows, int32_t* __restrict__ amb_count,
@@ -503,19 +504,28 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   for (int w = 1; w < kFilterWaves; ++w) cm2 = fmaxf(cm2, red[w]);
   const float Cm = sqrtf(cm2) * 1.00002f;  // upper bound
 
+  // RESIDENT (the caller's choice when Cpad <= 2 kCentChunk: both LDS stages hold their chunk of
+  // centroids for good): the workgroup takes several groups of rows, one after the other - the
+  // table above, the chunk copies and the barriers are paid once, and while one workgroup of a
+  // CU fetches its next rows the other one computes. Otherwise the grid has one workgroup per
+  // group of rows.
+  int64_t grp = blockIdx.x;
+  do {
   // B operands: rows of two 32-row sets, dims 16s + 8 lh .. +7
   int64_t rows[2];
   bool valid[2];
+  int cur[2] = {-1, -1};  // the rows' present labels, fetched with the rows (the epilogue compares them)
   bf16x8 bx[2][KSN];
 #pragma unroll
   for (int rs = 0; rs < 2; ++rs) {
-    const int64_t pos = (int64_t)blockIdx.x * kFilterRows + kFilterRowsPerWave * wave + 32 * rs + li;
+    const int64_t pos = grp * kFilterRows + kFilterRowsPerWave * wave + 32 * rs + li;
     valid[rs] = pos < n_rows;
     const int64_t lpos = valid[rs] ? pos : n_rows - 1;
     rows[rs] = row_list ? row_list[(int64_t)bh * nv + lpos] : lpos;
     const bf16_t* xr = x + head_base(st, bh, H) + rows[rs] * st.n;
 #pragma unroll
     for (int s = 0; s < KSN; ++s) bx[rs][s] = as_bf16x8(*reinterpret_cast<const uint4*>(xr + 16 * s + 8 * lh));
+    if (dirty && lh == 0) cur[rs] = labels[(int64_t)bh * nv + rows[rs]];
   }
   SVGEAR_WAIT_VMCNT(0);
   // |x|_2 of the rows, rounded up, computed from the operands the lane holds - each lane squares
@@ -617,25 +627,31 @@ assign_filter_kernel(const bf16_t* __restrict__ x, Strides st, int H, int64_t nv
   };
 
   // prologue: chunks 0 and 1 in flight, block 0 accumulated
-  issue_chunk(0);
-  if (nchunks > 1) issue_chunk(1);
-  SVGEAR_WAIT_VMCNT(0);
-  __syncthreads();
+  if (!RESIDENT || grp == blockIdx.x) {
+    issue_chunk(0);
+    if (nchunks > 1) issue_chunk(1);
+    SVGEAR_WAIT_VMCNT(0);
+    __syncthreads();
+  }
   step(-1, true, accB0, accB1, accA0, accA1);  // accumulates block 0 into A (nothing to rank yet)
   for (int ch = 0; ch < nchunks; ++ch) {
     // block 2ch+1 (same chunk) into B while ranking block 2ch from A
     step(2 * ch, true, accA0, accA1, accB0, accB1);
-    // stage ch&1 is now free for chunk ch+2, and chunk ch+1 (issued one iteration ago) has landed
-    SVGEAR_WAIT_VMCNT(0);
-    __syncthreads();
-    if (ch + 2 < nchunks) issue_chunk(ch + 2);
+    if (!RESIDENT) {
+      // stage ch&1 is now free for chunk ch+2, and chunk ch+1 (issued one iteration ago) has landed
+      SVGEAR_WAIT_VMCNT(0);
+      __syncthreads();
+      if (ch + 2 < nchunks) issue_chunk(ch + 2);
+    }
     // block 2ch+2 (next chunk) into A while ranking block 2ch+1 from B
     step(2 * ch + 1, ch + 1 < nchunks, accB0, accB1, accA0, accA1);
   }
 #pragma unroll
   for (int rs = 0; rs < 2; ++rs)
-    settle_row<D>(best[rs], second[rs], arg[rs], valid[rs], rows[rs], xn[rs], Cm, INFINITY, nullptr, -1, bh, nv, Cpad,
-                  labels, amb_rows, amb_count, bnd, dirty);
+    settle_row<D>(best[rs], second[rs], arg[rs], valid[rs], rows[rs], xn[rs], Cm, INFINITY, nullptr, cur[rs], bh, nv,
+                  Cpad, labels, amb_rows, amb_count, bnd, dirty);
+  grp += gridDim.x;
+  } while (RESIDENT && grp * kFilterRows < n_rows);
 }
 
 constexpr int kBoundRows = 8;  // rows per thread of bounds_update_kernel
@@ -1258,7 +1274,9 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const size_t lds_f = 2 * (size_t)kCentChunk * D * 4 + ((size_t)Cpad + 64 * kFilterWaves) * sizeof(float);
   if constexpr (kFilter) {
-    SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D>),
+    SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
+    SVGEAR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_filter_kernel<D, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f));
   }
   const dim3 gp((unsigned)ceil_div((int64_t)Cpad * D, 256 * 4), BH);
@@ -1282,12 +1300,16 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
                                              dirty);
     SVGEAR_LAUNCH_CHECK();
     if constexpr (kFilter) {
-      const dim3 gf((unsigned)ceil_div(nv, kFilterRows), BH), gb((unsigned)ceil_div(nv, 256 * kBoundRows), BH);
+      // (with at most two chunks of centroids a workgroup of the filter takes several groups of rows)
+      const bool resident = Cpad <= 2 * kCentChunk;
+      auto filter = resident ? assign_filter_kernel<D, true> : assign_filter_kernel<D, false>;
+      const dim3 gf((unsigned)ceil_div(ceil_div(nv, kFilterRows), resident ? kFilterGroups : 1), BH);
+      const dim3 gb((unsigned)ceil_div(nv, 256 * kBoundRows), BH);
       const bf16_t* xb = reinterpret_cast<const bf16_t*>(x);
       if (it == 0) {
         // every row against every centroid
-        assign_filter_kernel<D><<<gf, 64 * kFilterWaves, lds_f, s>>>(
-            xb, st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count, nullptr, nullptr, bnd, nullptr);
+        filter<<<gf, 64 * kFilterWaves, lds_f, s>>>(xb, st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count,
+                                                    nullptr, nullptr, bnd, nullptr);
         SVGEAR_LAUNCH_CHECK();
       } else {
         // only the rows whose bounds do not prove that their label stays
@@ -1311,8 +1333,8 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
         // the queued rows (all flagged rows, or those of the clusters without a list) against
         // every centroid; the grid covers every row, workgroups beyond the queue's length leave
         // at once
-        assign_filter_kernel<D><<<gf, 64 * kFilterWaves, lds_f, s>>>(
-            xb, st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count, act_rows, head_state, bnd, dirty);
+        filter<<<gf, 64 * kFilterWaves, lds_f, s>>>(xb, st, H, nv, chl, cn, xnorm, C, Cpad, labels, amb_rows, amb_count,
+                                                    act_rows, head_state, bnd, dirty);
         SVGEAR_LAUNCH_CHECK();
       }
       assign_few_kernel<T, D><<<dim3((unsigned)ceil_div(nv, 32 * 8), BH), 256, 0, s>>>(
