@@ -91,6 +91,33 @@ def test_kmeans_free_running_matches_oracle(later_iterations_mode):
         assert np.array_equal(to_np(counts[0, 0]), n_ref)
 
 
+def test_kmeans_zero_rows_and_a_zero_centroid(later_iterations_mode):
+    """All-zero rows (padding tokens) against a table that holds the zero vector several times:
+    their winning score is exactly 0 and tied, so the lowest index among the zero centroids must
+    win; one head also has rows and scores deep in the small numbers."""
+    g = torch.Generator(device="cpu").manual_seed(11)
+    n, d, C = 3000, 128, 70
+    X = torch.randn(1, 2, n, d, generator=g)
+    X[:, :, 100:900] = 0.0
+    X[:, 1, 2000:2100] *= 1e-20          # rows and scores deep in the small numbers
+    X = X.to(torch.bfloat16).to(dev()).contiguous()
+    c0 = X[:, :, torch.randperm(n, generator=g)[:C]].float().contiguous()
+    c0[:, :, 37] = 0.0                   # the zero centroid, not at index 0
+    c0[:, 1, 5] = X[0, 1, 2050].float()
+    prev = c0.clone()
+    for iters in (1, 2, 3):
+        cur = c0.clone()
+        lab, cnt, _ = sv.kmeans(X, cur, iters)
+        torch.cuda.synchronize()
+        for h in range(2):
+            ref = orc.kmeans_assign(to_np(X[0, h]), to_np((c0 if iters == 1 else prev)[0, h]))
+            assert np.array_equal(to_np(lab[0, h]), ref), f"iters {iters} head {h}"
+            if iters == 1:
+                zero = np.flatnonzero(np.all(to_np(c0[0, h]) == 0.0, axis=1))
+                assert 37 in zero and np.all(ref[100:900] == zero.min())
+        prev = cur
+
+
 def test_kmeans_edge_cases():
     g = torch.Generator(device="cpu").manual_seed(0)
     # C = 1, N not a multiple of any tile, d = 128 fp32
