@@ -45,6 +45,28 @@ def attention_source_hash() -> str:
     return h.hexdigest()[:16]
 
 
+def vendor_gemm_rate():
+    """What the vendor's own bf16 GEMM (torch.matmul, 8192^3, 100 calls back to back) sustains on this
+    GPU: context for `roofline.frac`, whose peak is the published one."""
+    import torch
+    try:
+        n = 8192
+        a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+        b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+        for _ in range(5):
+            a @ b
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(100):
+            a @ b
+        e1.record()
+        torch.cuda.synchronize()
+        return {"torch_matmul_bf16_8192_tflops": 2.0 * n ** 3 * 100 / (e0.elapsed_time(e1) * 1e-3) / 1e12}
+    except Exception as ex:  # noqa: BLE001
+        return {"torch_matmul_error": str(ex)[:200]}
+
+
 def measured_attention_traffic(workload: str, rho: float, heads: int):
     """Bytes per launch from the tracked file, or None if no line matches this workload, budget, head
     count and the current kernel sources. Line format: workload rho heads source_hash bytes."""
@@ -569,7 +591,8 @@ def main():
         except Exception as ex:  # noqa: BLE001
             sd = {"torch_sdpa_error": str(ex)[:200]}
         out["dense_bracket"] = {"own_kernel_all_routed_ms": own_ms,
-                                "own_kernel_all_routed_tflops": dense_flops / (own_ms * 1e-3) / 1e12, **sd}
+                                "own_kernel_all_routed_tflops": dense_flops / (own_ms * 1e-3) / 1e12, **sd,
+                                **vendor_gemm_rate()}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(orc, wl, Q, K, V, cq0, ck0, budget)
