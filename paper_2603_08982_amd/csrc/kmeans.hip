@@ -163,13 +163,12 @@ __device__ __forceinline__ void load_row_operands(const bf16_t* xr, int h, float
 // (min, argmin) in ascending centroid order; the two lanes of a row merge once at the end.
 // Centroid chunks (64 centroids, in operand order) stream through two LDS stages with
 // asynchronous global-to-LDS copies shared by the 8 waves (256 rows) of the workgroup.
-// With row_list != nullptr only the rows listed there (row_count[bh] of them) are assigned.
+// (Every row of fp32 inputs goes through this kernel; of bf16 inputs only the rows the filter
+// below cannot decide, through assign_few_kernel.)
 template <typename T, int D>
 __global__ void __launch_bounds__(64 * kAssignWaves)
 assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const float* __restrict__ cperm,
-                   const float* __restrict__ cn, int Cpad, int32_t* __restrict__ labels,
-                   const int32_t* __restrict__ row_list, const int32_t* __restrict__ row_count,
-                   int32_t* __restrict__ dirty) {
+                   const float* __restrict__ cn, int Cpad, int32_t* __restrict__ labels) {
   constexpr int QG = D / 8;                        // 16-byte operand groups per block
   constexpr int CHUNK_BYTES = kCentChunk * D * 4;  // one LDS stage of centroids
   constexpr int COPIES = CHUNK_BYTES / 1024 / kAssignWaves;
@@ -179,14 +178,8 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const int bh = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t n_rows = row_list ? row_count[bh] : nv;
-  // block-stride loop over 256-row tiles: the refinement pass, whose row list is short and of
-  // unknown length at launch, runs on a quarter of the full grid (workgroups that find nothing
-  // to do still hold a slot until their row count arrives)
-  for (int64_t blk = blockIdx.x; blk * kAssignRows < n_rows; blk += gridDim.x) {
-  const int64_t pos = blk * kAssignRows + 32 * wave + li;
-  const int64_t lpos = pos < n_rows ? pos : n_rows - 1;
-  const int64_t row = row_list ? row_list[(int64_t)bh * nv + lpos] : lpos;
+  const int64_t pos = (int64_t)blockIdx.x * kAssignRows + 32 * wave + li;
+  const int64_t row = pos < nv ? pos : nv - 1;
   float xb[D / 2];
   load_row_operands<D>(x + head_base(st, bh, H) + row * st.n, lh, xb);
   SVGEAR_WAIT_VMCNT(0);  // rows are in registers before the asynchronous copies start
@@ -265,18 +258,7 @@ assign_mfma_kernel(const T* __restrict__ x, Strides st, int H, int64_t nv, const
   const float ob = __shfl_xor(best, 32);
   const int oa = __shfl_xor(arg, 32);
   if (ob < best || (ob == best && oa < arg)) arg = oa;
-  if (lh == 0 && pos < n_rows) {
-    if (dirty) {  // a row that moves marks the cluster it leaves and the one it joins
-      const int cur = labels[(int64_t)bh * nv + row];
-      if (cur != arg) {
-        dirty[(int64_t)bh * Cpad + cur] = 1;
-        dirty[(int64_t)bh * Cpad + arg] = 1;
-      }
-    }
-    labels[(int64_t)bh * nv + row] = arg;
-  }
-  __syncthreads();  // the LDS stages are refilled by the next tile
-  }
+  if (lh == 0 && pos < nv) labels[(int64_t)bh * nv + row] = arg;
 }
 
 // The same assignment for a short list of rows (the filter's ambiguous ones): with few rows
@@ -1340,7 +1322,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
       assign_few_kernel<T, D><<<dim3((unsigned)ceil_div(nv, 32 * 8), BH), 256, 0, s>>>(
           x, st, H, nv, cperm, cn, Cpad, labels, amb_rows, amb_count, it > 0 ? dirty : nullptr);
     } else {
-      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels, nullptr, nullptr, nullptr);
+      assign<<<ga, 64 * kAssignWaves, lds, s>>>(x, st, H, nv, cperm, cn, Cpad, labels);
     }
     SVGEAR_LAUNCH_CHECK();
     int rc = sort_labels(labels, BH, nv, 0, C, perm, offsets, chunk_hist, s, use_lists ? tiles : nullptr, tile_cap,
