@@ -96,7 +96,7 @@ int svgear_kmeans(const void* x, const void* x2, svgear_dtype dt, int B, int H, 
  * C >= the value set here each such row is tested against the centroids near its cluster only
  * (candidate lists from centroid-to-centroid distances); with fewer centroids against all of
  * them. min_centroids >= 1 sets the threshold for later calls of this process (INT_MAX: never
- * use lists); min_centroids <= 0 only queries. Returns the previous value (default 513). */
+ * use lists); min_centroids <= 0 only queries. Returns the previous value (default 400). */
 int svgear_kmeans_list_threshold(int min_centroids);
 
 /* ---------------------------------------------------------------------------------------

@@ -41,7 +41,13 @@ constexpr int kListChunk = 4 * kListTile;       // sorted positions per wave (on
 constexpr int kMaxCentroids = 8192;             // most centroids per head the entry point accepts
 // Candidate lists pay when there are many centroids: with fewer than this, testing every
 // centroid (shared through LDS by 256 rows, streaming) costs no more than the lists' gathers.
-std::atomic<int> g_list_min_centroids{513};
+std::atomic<int> g_list_min_centroids{400};
+// (in the second iteration of a cold start the radii still reach every centroid, so no cluster gets
+// a list: the lists start one iteration later)
+#ifndef SVGEAR_LIST_FROM
+#define SVGEAR_LIST_FROM 2
+#endif
+constexpr int kListFromIteration = SVGEAR_LIST_FROM;
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
@@ -1295,7 +1301,7 @@ int run_kmeans(const T* x, const T* x2, int BH, int H, int64_t N, int64_t n_tail
         SVGEAR_LAUNCH_CHECK();
       } else {
         // only the rows whose bounds do not prove that their label stays
-        if (use_lists) {
+        if (use_lists && it >= kListFromIteration) {
           // ... each against the centroids near its cluster
           bounds_update_kernel<D, true><<<gb, 256, 0, s>>>(labels, xnorm, cn, drift, C, Cpad, nv, bnd, act_rows, rank,
                                                            prow, rmax, head_state);

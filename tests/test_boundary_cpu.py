@@ -38,7 +38,7 @@ def test_kmeans_list_threshold_sets_and_queries(lib):
     lib.svgear_kmeans_list_threshold.restype = ctypes.c_int
     lib.svgear_kmeans_list_threshold.argtypes = [ctypes.c_int]
     default = lib.svgear_kmeans_list_threshold(0)
-    assert default == 513
+    assert default == 400
     assert lib.svgear_kmeans_list_threshold(7) == default
     assert lib.svgear_kmeans_list_threshold(-3) == 7      # query only
     assert lib.svgear_kmeans_list_threshold(default) == 7
