@@ -13,9 +13,19 @@ from helpers import dev, init_centroids
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["default", "candidate_lists"])
+def kmeans_mode(request):
+    """The library's default, and the later k-means iterations forced onto candidate lists (more
+    kernels, queues filled through atomics) whatever the number of centroids."""
+    from paper_2603_08982_amd.binding import kmeans_list_threshold
+    before = kmeans_list_threshold(1) if request.param == "candidate_lists" else kmeans_list_threshold(0)
+    yield request.param
+    kmeans_list_threshold(before)
+
+
 @pytest.mark.parametrize("overlap", [False, True])
 @pytest.mark.parametrize("name", ["mini_video", "mini_video_tail"])
-def test_captured_layer_replays_bit_exactly(name, overlap):
+def test_captured_layer_replays_bit_exactly(name, overlap, kmeans_mode):
     wl = get_workload(name)
     Q, K, V = make_qkv(wl, dev())
     cq0 = init_centroids(Q, wl.Cq, wl.seed, 0, wl.n_tail)
